@@ -1,0 +1,31 @@
+"""MI355X-native fused LM-head log-probability objective (HIP, gfx950).
+
+Thin Python binding over the C ABI declared in ``include/lmhead.h``.  PyTorch is
+used only to own device memory and streams; every step of the path runs in the
+library's HIP kernels.  There is no CPU fallback: if the shared library is
+missing or no GPU is present, the compute entry points raise.
+"""
+from .binding import (
+    LmheadError,
+    LmheadDesc,
+    library_path,
+    load_library,
+    make_desc,
+    workspace_bytes,
+    loss_workspace_bytes,
+    validate_desc,
+    lmhead_logprob_fwd,
+    lmhead_logprob_bwd,
+    group_advantage,
+    grpo_loss,
+    flowrl_tb_loss,
+    lmhead_check,
+    EXPORTED_SYMBOLS,
+)
+
+__all__ = [
+    "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
+    "workspace_bytes", "loss_workspace_bytes", "validate_desc",
+    "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
+    "flowrl_tb_loss", "lmhead_check", "EXPORTED_SYMBOLS",
+]

@@ -1,0 +1,179 @@
+// Shared internal declarations of the lmhead library: workspace layout, launcher
+// prototypes and small device helpers.  Nothing here is part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lmhead.h"
+
+namespace lmhead {
+
+// Macro-tile of every contraction: 256 x 256 outputs, K consumed 128 bytes per row per step.
+constexpr int kTile = 256;
+constexpr int kKBytes = 128;
+
+// Sticky error bits written by kernels into WsHeader::err.
+constexpr int kErrLen = 1;  // a length outside [0, T]
+constexpr int kErrTok = 2;  // a token id outside [0, V) on a valid slot
+
+struct WsHeader {
+  int32_t err;  // sticky error bits
+  int32_t nv;   // number of valid slots N_v (written by the index kernel)
+  int32_t pad[62];
+};
+static_assert(sizeof(WsHeader) == 256, "header is one 256-byte line");
+
+static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// Byte offsets of every workspace region for one descriptor.  All regions are
+// 256-byte aligned.  "cap" sizes are worst cases (every slot valid) because
+// N_v lives on the device.
+struct WsLayout {
+  int esz;          // element size of H/W in bytes
+  int64_t N, R;     // slots, responses
+  int64_t Ncap;     // N rounded up to the tile
+  int64_t Vp;       // V rounded up to the tile
+  int64_t dp;       // d rounded up to the tile
+  int64_t Vc;       // vocabulary chunk (multiple of the tile)
+  int64_t nchunks;  // number of vocabulary chunks
+  size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, total;
+};
+
+static inline int64_t default_vocab_chunk(const lmhead_desc* d) {
+  (void)d;
+  return 8192;
+}
+
+static inline WsLayout make_layout(const lmhead_desc* d) {
+  WsLayout L{};
+  L.esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
+  L.R = (int64_t)d->P * d->G;
+  L.N = L.R * d->T;
+  L.Ncap = (int64_t)round_up((size_t)L.N, kTile);
+  L.Vp = (int64_t)round_up((size_t)d->V, kTile);
+  L.dp = (int64_t)round_up((size_t)d->d, kTile);
+  int64_t vc = d->vocab_chunk > 0 ? d->vocab_chunk : default_vocab_chunk(d);
+  vc = (int64_t)round_up((size_t)vc, kTile);
+  if (vc > L.Vp) vc = L.Vp;
+  L.Vc = vc;
+  L.nchunks = (L.Vp + vc - 1) / vc;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return o;
+  };
+  L.hdr = take(sizeof(WsHeader));
+  L.cu_len = take((size_t)(L.R + 1) * 4);
+  L.row_slot = take((size_t)L.Ncap * 4);
+  L.tok_c = take((size_t)L.Ncap * 4);
+  L.g_c = take((size_t)L.Ncap * 4);
+  L.lse_c = take((size_t)L.Ncap * 4);
+  L.zy = take((size_t)L.Ncap * 4);
+  L.part = take((size_t)3 * L.nchunks * L.Ncap * 4);
+  L.Hc = take((size_t)L.Ncap * d->d * L.esz);
+  L.HcT = take((size_t)L.dp * L.Ncap * L.esz);
+  L.WT = take((size_t)L.dp * L.Vp * L.esz);
+  L.dZ = take((size_t)L.Ncap * L.Vc * L.esz);
+  L.dZT = take((size_t)L.Vc * L.Ncap * L.esz);
+  L.total = off;
+  return L;
+}
+
+// ---- launchers (each enqueues on `s` and returns hipGetLastError()) --------------------
+
+// lens -> cu_len, header.nv, mask, row_slot (padded with -1 up to the next tile multiple).
+hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t* cu_ws,
+                        int32_t* row_slot, uint8_t* mask_out, int32_t* cu_out, hipStream_t s);
+
+// Gathers the valid rows of H into the dense, zero-padded Hc[Ncap x d]; also compacts tok
+// (range-checked), and optionally g_logp and lse.  zy is cleared.
+hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
+                          const float* g, const float* lse, int64_t N, WsHeader* hdr,
+                          const int32_t* row_slot, void* Hc, int32_t* tok_c, float* g_c,
+                          float* lse_c, float* zy, hipStream_t s);
+
+// out[c][r] = in[r][c] for r < rows (rows read from the header when rows_from_nv), zero padding
+// up to out's full extent [cols_p x ld_out].
+hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows_cap, int cols,
+                            bool rows_from_nv, const WsHeader* hdr, void* out, int64_t ld_out,
+                            int64_t cols_p, hipStream_t s);
+
+struct FwdArgs {
+  const void* Hc;      // [Ncap x d] dense
+  const void* W;       // [V x d], stride ldW
+  int64_t ldW;
+  int d, V;
+  int64_t Ncap;
+  int tiles_per_chunk; // vocabulary tiles each workgroup walks
+  int nchunks;
+  const int32_t* tok_c;
+  const WsHeader* hdr;
+  float* part;         // [3][nchunks][Ncap]
+  float* zy;           // [Ncap]
+};
+hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s);
+
+// Merges the per-chunk partials and scatters logp / lse / entropy to slot order (0 on padding).
+hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int64_t Ncap,
+                           const int32_t* len, const int32_t* cu_len, int R, int T, float* logp,
+                           float* lse, float* entropy, hipStream_t s);
+
+struct DzArgs {
+  const void* Hc;
+  const void* W;
+  int64_t ldW;
+  int d, V;
+  int64_t Ncap;
+  int64_t Vc;     // chunk width (columns of dZ)
+  int c0;         // first vocabulary id of the chunk
+  int ntiles;     // vocabulary tiles in this chunk
+  const int32_t* tok_c;
+  const float* g_c;
+  const float* lse_c;
+  const WsHeader* hdr;
+  void* dZ;       // [Ncap x Vc]
+  void* dZT;      // [Vc x Ncap]
+};
+hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s);
+
+// Generic C^T-store contraction: for m < M, n < Nn: out[rowmap(n)][m] (+)= sum_k A[m][k] B[n][k].
+struct GemmTArgs {
+  const void* A;       // [Mp x K], pitch ldA elements
+  int64_t ldA;
+  const void* B;       // [Np x K], pitch ldB elements
+  int64_t ldB;
+  int M;               // valid output columns (d)
+  int64_t n_limit;     // valid n (ignored when n_from_nv)
+  bool n_from_nv;      // n extent = header.nv (dH); else n_limit (dW)
+  bool k_from_nv;      // K extent = header.nv rounded up (dW); else K
+  int64_t K;           // contraction length in elements (multiple of 128/esz)
+  const int32_t* rowmap;  // output row of n, or NULL for identity + row_base
+  int64_t row_base;
+  float* out;          // dense rows of M floats
+  int64_t ldo;
+  bool accumulate;
+  int64_t n_tiles_cap; // grid extent over n
+  const WsHeader* hdr;
+};
+hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s);
+
+// Rows of dH that belong to padded slots are set to 0.
+hipError_t launch_zero_padded_rows(float* dH, int d, const int32_t* len, int R, int T,
+                                   hipStream_t s);
+
+hipError_t launch_group_advantage(const float* reward, int P, int G, float eps, int ddof,
+                                  float* adv, hipStream_t s);
+hipError_t launch_grpo(const float* lp, const float* lo, const float* lr, const float* adv,
+                       const int32_t* len, int P, int G, int T, float clip_lo, float clip_hi,
+                       float kl, int agg, float* loss, float* g, float* stats, float* ws,
+                       hipStream_t s);
+hipError_t launch_flowrl(const float* lp, const float* lr, const float* reward, const float* logZ,
+                         const int32_t* len, int P, int G, int T, float beta, float* loss,
+                         float* g, float* gz, float* resid, float* ws, hipStream_t s);
+
+constexpr int kLossSlotsPerBlock = 2048;
+
+}  // namespace lmhead

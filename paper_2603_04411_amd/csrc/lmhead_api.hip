@@ -1,0 +1,244 @@
+// extern "C" entry points: host-side validation, workspace carving and kernel sequencing.
+// Every argument error is returned before anything is enqueued.
+#include "common.h"
+
+using namespace lmhead;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate(const lmhead_desc* d) {
+  if (!d) return LMHEAD_E_NULL;
+  if (d->P <= 0 || d->G <= 0 || d->T <= 0 || d->d <= 0 || d->V <= 0) return LMHEAD_E_SHAPE;
+  if (d->dtype != LMHEAD_F32 && d->dtype != LMHEAD_BF16) return LMHEAD_E_DTYPE;
+  if (d->flags & ~(uint32_t)LMHEAD_FLAG_ACCUM_DW) return LMHEAD_E_DTYPE;
+  if (d->reserved != 0 || d->reserved2 != 0 || d->vocab_chunk < 0) return LMHEAD_E_SHAPE;
+  if (d->d % 64 != 0) return LMHEAD_E_SHAPE;
+  if (d->ldH < d->d || d->ldW < d->d) return LMHEAD_E_SHAPE;
+  const int64_t R = (int64_t)d->P * d->G;
+  const int64_t N = R * d->T;
+  if (R > INT32_MAX || N > (int64_t)INT32_MAX - 2 * kTile) return LMHEAD_E_SHAPE;
+  if ((int64_t)d->V > (int64_t)INT32_MAX - 2 * kTile) return LMHEAD_E_SHAPE;
+  const int esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
+  if ((d->ldH * esz) % 16 != 0 || (d->ldW * esz) % 16 != 0) return LMHEAD_E_ALIGN;
+  return LMHEAD_OK;
+}
+
+struct Ws {
+  WsLayout L;
+  char* base;
+  template <typename T>
+  T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
+};
+
+#define LM_TRY(expr)                         \
+  do {                                       \
+    if ((expr) != hipSuccess) return LMHEAD_E_HIP; \
+  } while (0)
+
+size_t loss_ws_bytes(int64_t P, int64_t G, int64_t T) {
+  const int64_t R = P * G;
+  const int64_t nb = (T + kLossSlotsPerBlock - 1) / kLossSlotsPerBlock;
+  return (size_t)(R * nb * 4 + R) * sizeof(float) + 256;
+}
+
+int validate_pgt(int32_t P, int32_t G, int32_t T) {
+  if (P <= 0 || G <= 0 || T <= 0) return LMHEAD_E_SHAPE;
+  const int64_t R = (int64_t)P * G;
+  if (R > 65535 || R * T > INT32_MAX) return LMHEAD_E_SHAPE;  // R is a grid y-extent
+  return LMHEAD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lmhead_abi_version(void) { return 1; }
+
+int lmhead_validate_desc(const lmhead_desc* desc) { return validate(desc); }
+
+size_t lmhead_workspace_bytes(const lmhead_desc* desc) {
+  if (validate(desc) != LMHEAD_OK) return 0;
+  return make_layout(desc).total;
+}
+
+int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
+                       const int32_t* len, float* logp, float* lse, float* entropy, uint8_t* mask,
+                       int32_t* cu_len, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (!H || !W || !tok || !len || !logp || !ws) return LMHEAD_E_NULL;
+  if (!aligned16(H) || !aligned16(W) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LMHEAD_E_ALIGN;
+  Ws w{make_layout(desc), static_cast<char*>(ws)};
+  if (ws_bytes < w.L.total) return LMHEAD_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const WsLayout& L = w.L;
+  WsHeader* hdr = w.at<WsHeader>(L.hdr);
+
+  LM_TRY(launch_index(len, (int)L.R, desc->T, hdr, w.at<int32_t>(L.cu_len), w.at<int32_t>(L.row_slot),
+                      mask, cu_len, s));
+  LM_TRY(launch_compact(desc->dtype, H, desc->ldH, desc->d, desc->V, tok, nullptr, nullptr, L.N, hdr,
+                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), w.at<int32_t>(L.tok_c), nullptr,
+                        nullptr, w.at<float>(L.zy), s));
+  FwdArgs fa{};
+  fa.Hc = w.at<void>(L.Hc);
+  fa.W = W;
+  fa.ldW = desc->ldW;
+  fa.d = desc->d;
+  fa.V = desc->V;
+  fa.Ncap = L.Ncap;
+  fa.tiles_per_chunk = (int)(L.Vc / kTile);
+  fa.nchunks = (int)L.nchunks;
+  fa.tok_c = w.at<int32_t>(L.tok_c);
+  fa.hdr = hdr;
+  fa.part = w.at<float>(L.part);
+  fa.zy = w.at<float>(L.zy);
+  LM_TRY(launch_fwd(desc->dtype, fa, s));
+  LM_TRY(launch_finalize(w.at<float>(L.part), w.at<float>(L.zy), (int)L.nchunks, L.Ncap, len,
+                         w.at<int32_t>(L.cu_len), (int)L.R, desc->T, logp, lse, entropy, s));
+  return LMHEAD_OK;
+}
+
+int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
+                       const int32_t* len, const float* lse, const float* g_logp, float* dH, float* dW,
+                       void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (!H || !W || !tok || !len || !lse || !g_logp || !dH || !dW || !ws) return LMHEAD_E_NULL;
+  if (!aligned16(H) || !aligned16(W) || !aligned16(dH) || !aligned16(dW) ||
+      (reinterpret_cast<uintptr_t>(ws) & 255u))
+    return LMHEAD_E_ALIGN;
+  Ws w{make_layout(desc), static_cast<char*>(ws)};
+  if (ws_bytes < w.L.total) return LMHEAD_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const WsLayout& L = w.L;
+  WsHeader* hdr = w.at<WsHeader>(L.hdr);
+  const int dt = desc->dtype;
+
+  LM_TRY(launch_index(len, (int)L.R, desc->T, hdr, w.at<int32_t>(L.cu_len), w.at<int32_t>(L.row_slot),
+                      nullptr, nullptr, s));
+  LM_TRY(launch_compact(dt, H, desc->ldH, desc->d, desc->V, tok, g_logp, lse, L.N, hdr,
+                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), w.at<int32_t>(L.tok_c),
+                        w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), s));
+  // K-contiguous copies of the two operands that the backward contracts along their rows
+  LM_TRY(launch_transpose(dt, w.at<void>(L.Hc), desc->d, L.Ncap, desc->d, true, hdr, w.at<void>(L.HcT),
+                          L.Ncap, L.dp, s));
+  LM_TRY(launch_transpose(dt, W, desc->ldW, desc->V, desc->d, false, hdr, w.at<void>(L.WT), L.Vp, L.dp, s));
+  LM_TRY(launch_zero_padded_rows(dH, desc->d, len, (int)L.R, desc->T, s));
+
+  const int total_tiles = (int)(L.Vp / kTile);
+  const int tiles_per_chunk = (int)(L.Vc / kTile);
+  for (int c = 0; c < (int)L.nchunks; ++c) {
+    const int t_lo = c * tiles_per_chunk;
+    const int ntiles = (total_tiles - t_lo < tiles_per_chunk) ? total_tiles - t_lo : tiles_per_chunk;
+    const int c0 = t_lo * kTile;
+    DzArgs za{};
+    za.Hc = w.at<void>(L.Hc);
+    za.W = W;
+    za.ldW = desc->ldW;
+    za.d = desc->d;
+    za.V = desc->V;
+    za.Ncap = L.Ncap;
+    za.Vc = L.Vc;
+    za.c0 = c0;
+    za.ntiles = ntiles;
+    za.tok_c = w.at<int32_t>(L.tok_c);
+    za.g_c = w.at<float>(L.g_c);
+    za.lse_c = w.at<float>(L.lse_c);
+    za.hdr = hdr;
+    za.dZ = w.at<void>(L.dZ);
+    za.dZT = w.at<void>(L.dZT);
+    LM_TRY(launch_dz(dt, za, s));
+
+    // dH[slot(n)][m] (+)= sum_v W^T[m][c0 + v] dZ[n][v]
+    GemmTArgs ha{};
+    ha.A = w.at<char>(L.WT) + (size_t)c0 * L.esz;
+    ha.ldA = L.Vp;
+    ha.B = w.at<void>(L.dZ);
+    ha.ldB = L.Vc;
+    ha.M = desc->d;
+    ha.n_from_nv = true;
+    ha.k_from_nv = false;
+    ha.K = (int64_t)ntiles * kTile;
+    ha.rowmap = w.at<int32_t>(L.row_slot);
+    ha.out = dH;
+    ha.ldo = desc->d;
+    ha.accumulate = c > 0;
+    ha.n_tiles_cap = L.Ncap / kTile;
+    ha.hdr = hdr;
+    LM_TRY(launch_gemm_t(dt, ha, s));
+
+    // dW[c0 + n][m] = sum_i Hc^T[m][i] dZ^T[n][i]
+    GemmTArgs wa{};
+    wa.A = w.at<void>(L.HcT);
+    wa.ldA = L.Ncap;
+    wa.B = w.at<void>(L.dZT);
+    wa.ldB = L.Ncap;
+    wa.M = desc->d;
+    wa.n_limit = (desc->V - c0 < ntiles * kTile) ? desc->V - c0 : ntiles * kTile;
+    wa.n_from_nv = false;
+    wa.k_from_nv = true;
+    wa.rowmap = nullptr;
+    wa.row_base = c0;
+    wa.out = dW;
+    wa.ldo = desc->d;
+    wa.accumulate = (desc->flags & LMHEAD_FLAG_ACCUM_DW) != 0;
+    wa.n_tiles_cap = ntiles;
+    wa.hdr = hdr;
+    LM_TRY(launch_gemm_t(dt, wa, s));
+  }
+  return LMHEAD_OK;
+}
+
+int group_advantage(const float* reward, int32_t P, int32_t G, float eps, int32_t ddof, float* adv,
+                    void* stream) {
+  if (P <= 0 || G <= 0 || (int64_t)P * G > INT32_MAX) return LMHEAD_E_SHAPE;
+  if (ddof != 0 && ddof != 1) return LMHEAD_E_SHAPE;
+  if (!reward || !adv) return LMHEAD_E_NULL;
+  LM_TRY(launch_group_advantage(reward, P, G, eps, ddof, adv, static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
+size_t lmhead_loss_workspace_bytes(int32_t P, int32_t G, int32_t T) {
+  if (validate_pgt(P, G, T) != LMHEAD_OK) return 0;
+  return loss_ws_bytes(P, G, T);
+}
+
+int grpo_loss(const float* logp, const float* logp_old, const float* logp_ref, const float* adv,
+              const int32_t* len, int32_t P, int32_t G, int32_t T, float clip_lo, float clip_hi,
+              float kl_coef, int32_t agg_mode, float* loss, float* g_logp, float* stats, void* ws,
+              size_t ws_bytes, void* stream) {
+  const int rc = validate_pgt(P, G, T);
+  if (rc != LMHEAD_OK) return rc;
+  if (agg_mode != 0 && agg_mode != 1) return LMHEAD_E_SHAPE;
+  if (!logp || !logp_old || !adv || !len || !loss || !ws) return LMHEAD_E_NULL;
+  if (ws_bytes < loss_ws_bytes(P, G, T)) return LMHEAD_E_WORKSPACE;
+  LM_TRY(launch_grpo(logp, logp_old, logp_ref, adv, len, P, G, T, clip_lo, clip_hi, kl_coef, agg_mode,
+                     loss, g_logp, stats, static_cast<float*>(ws), static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
+int flowrl_tb_loss(const float* logp, const float* logp_ref, const float* reward, const float* logZ,
+                   const int32_t* len, int32_t P, int32_t G, int32_t T, float beta, float* loss,
+                   float* g_logp, float* g_logZ, float* resid, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate_pgt(P, G, T);
+  if (rc != LMHEAD_OK) return rc;
+  if (!logp || !logp_ref || !reward || !logZ || !len || !loss || !ws) return LMHEAD_E_NULL;
+  if (ws_bytes < loss_ws_bytes(P, G, T)) return LMHEAD_E_WORKSPACE;
+  LM_TRY(launch_flowrl(logp, logp_ref, reward, logZ, len, P, G, T, beta, loss, g_logp, g_logZ, resid,
+                       static_cast<float*>(ws), static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
+int lmhead_check(void* ws, void* stream) {
+  if (!ws) return LMHEAD_E_NULL;
+  WsHeader h;
+  if (hipMemcpyAsync(&h, ws, sizeof(int32_t) * 2, hipMemcpyDeviceToHost,
+                     static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LMHEAD_E_HIP;
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return LMHEAD_E_HIP;
+  return h.err != 0 ? LMHEAD_E_RANGE : LMHEAD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,279 @@
+// Bandwidth-bound helper kernels around the MFMA kernels: batch indexing (mask, prefix
+// sums, compaction map), row gather of H, operand transposes, the per-chunk merge of the
+// softmax statistics, and zero-filling of padded dH rows.  All accesses are coalesced
+// (16-byte vectors where rows allow); none of these kernels is more than a few passes
+// over O(N d + V d) bytes.
+#include "common.h"
+
+namespace lmhead {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- indexing --------------------------------------------------------------------------
+
+// One workgroup: exclusive prefix sum of the (clamped) lengths.
+__global__ __launch_bounds__(1024) void scan_len_kernel(const int32_t* __restrict__ len, int R, int T,
+                                                        WsHeader* hdr, int32_t* __restrict__ cu_ws,
+                                                        int32_t* __restrict__ cu_out) {
+  __shared__ int32_t wsum[16];
+  __shared__ int32_t carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) {
+    carry_s = 0;
+    hdr->err = 0;  // this kernel is the first of every call: reset the sticky word here
+  }
+  int bad = 0;
+  __syncthreads();
+  for (int base = 0; base < R; base += 1024) {
+    const int r = base + tid;
+    int x = 0;
+    if (r < R) {
+      x = len[r];
+      if (x < 0 || x > T) {
+        bad = 1;
+        x = x < 0 ? 0 : T;
+      }
+    }
+    int incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int woff = 0;
+    for (int w = 0; w < wave; ++w) woff += wsum[w];
+    const int carry = carry_s;
+    const int excl = carry + woff + incl - x;
+    if (r < R) {
+      cu_ws[r] = excl;
+      if (cu_out) cu_out[r] = excl;
+    }
+    __syncthreads();
+    if (tid == 1023) carry_s = excl + x;
+    __syncthreads();
+  }
+  if (bad) atomicOr(&hdr->err, kErrLen);
+  if (tid == 0) {
+    const int total = carry_s;
+    cu_ws[R] = total;
+    if (cu_out) cu_out[R] = total;
+    hdr->nv = total;
+  }
+}
+
+// One thread per slot (plus one tile of tail threads that pad row_slot with -1).
+__global__ __launch_bounds__(256) void fill_index_kernel(const int32_t* __restrict__ len, int R, int T,
+                                                         const int32_t* __restrict__ cu,
+                                                         int32_t* __restrict__ row_slot,
+                                                         uint8_t* __restrict__ mask) {
+  const int64_t N = (int64_t)R * T;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < N) {
+    const int r = (int)(i / T);
+    const int t = (int)(i - (int64_t)r * T);
+    const int n = min(max(len[r], 0), T);
+    const bool valid = t < n;
+    if (mask) mask[i] = valid ? 1 : 0;
+    if (valid) row_slot[cu[r] + t] = (int32_t)i;
+  } else {
+    const int64_t nv = cu[R];
+    const int64_t k = nv + (i - N);
+    const int64_t cap = (N + kTile - 1) / kTile * kTile;
+    if (i - N < kTile && k < cap) row_slot[k] = -1;
+  }
+}
+
+// ---- gather of valid rows ------------------------------------------------------------
+
+// One wavefront per compact row k: copies H[row_slot[k], :] (16 bytes per lane per step) or
+// zero-fills the rows between N_v and the next tile multiple.
+__global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H, int64_t pitchH,
+                                                      int row_bytes, int V,
+                                                      const int32_t* __restrict__ tok,
+                                                      const float* __restrict__ g,
+                                                      const float* __restrict__ lse, WsHeader* hdr,
+                                                      const int32_t* __restrict__ row_slot,
+                                                      char* __restrict__ Hc, int32_t* __restrict__ tok_c,
+                                                      float* __restrict__ g_c, float* __restrict__ lse_c,
+                                                      float* __restrict__ zy) {
+  const int nv = hdr->nv;
+  const int64_t nvp = ((int64_t)nv + kTile - 1) / kTile * kTile;
+  const int64_t k = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (k >= nvp) return;
+  const int lane = threadIdx.x & 63;
+  typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+  u4* dst = reinterpret_cast<u4*>(Hc + k * (int64_t)row_bytes);
+  const int nvec = row_bytes / 16;
+  if (k < nv) {
+    const int64_t slot = row_slot[k];
+    const u4* src = reinterpret_cast<const u4*>(H + slot * pitchH);
+    for (int c = lane; c < nvec; c += 64) dst[c] = src[c];
+    if (lane == 0) {
+      int tk = tok[slot];
+      if (tk < 0 || tk >= V) {
+        atomicOr(&hdr->err, kErrTok);
+        tk = -1;
+      }
+      tok_c[k] = tk;
+      if (g_c) g_c[k] = g[slot];
+      if (lse_c) lse_c[k] = lse[slot];
+      zy[k] = 0.f;
+    }
+  } else {
+    const u4 z = {0, 0, 0, 0};
+    for (int c = lane; c < nvec; c += 64) dst[c] = z;
+    if (lane == 0) {
+      tok_c[k] = -1;
+      if (g_c) g_c[k] = 0.f;
+      if (lse_c) lse_c[k] = 0.f;
+      zy[k] = 0.f;
+    }
+  }
+}
+
+// ---- transpose -------------------------------------------------------------------------
+
+// out[c][r] = in[r][c] through a 64x64 LDS tile; rows >= `rows` and columns >= `cols` of the
+// source read as zero, so the padded extent of `out` is zero-filled.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int64_t ld_in,
+                                                        int64_t rows_fixed, int cols, int rows_from_nv,
+                                                        const WsHeader* __restrict__ hdr,
+                                                        T* __restrict__ out, int64_t ld_out,
+                                                        int64_t cols_p) {
+  __shared__ T tile[64][65];
+  const int64_t rows = rows_from_nv ? (int64_t)hdr->nv : rows_fixed;
+  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int64_t c0 = (int64_t)blockIdx.y * 64;
+  if (rows_from_nv) {
+    // nothing beyond the tile-padded valid extent is ever read by the contractions
+    const int64_t rp = (rows + kTile - 1) / kTile * kTile;
+    if (r0 >= rp) return;
+  }
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int64_t r = r0 + rr, c = c0 + tx;
+    tile[rr][tx] = (r < rows && c < cols) ? in[r * ld_in + c] : T(0);
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int64_t c = c0 + cc, r = r0 + tx;
+    if (c < cols_p && r < ld_out) out[c * ld_out + r] = tile[tx][cc];
+  }
+}
+
+// ---- merge of per-chunk softmax statistics -------------------------------------------
+
+__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ part,
+                                                       const float* __restrict__ zy, int nchunks,
+                                                       int64_t Ncap, const int32_t* __restrict__ len,
+                                                       const int32_t* __restrict__ cu, int R, int T,
+                                                       float* __restrict__ logp, float* __restrict__ lse,
+                                                       float* __restrict__ ent) {
+  const int64_t N = (int64_t)R * T;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= N) return;
+  const int r = (int)(i / T);
+  const int t = (int)(i - (int64_t)r * T);
+  const int n = min(max(len[r], 0), T);
+  float o_lp = 0.f, o_lse = 0.f, o_ent = 0.f;
+  if (t < n) {
+    const int64_t k = cu[r] + t;
+    const size_t plane = (size_t)nchunks * Ncap;
+    float m = -__builtin_huge_valf();
+    for (int c = 0; c < nchunks; ++c) m = fmaxf(m, part[(size_t)c * Ncap + k]);
+    float s = 0.f, tt = 0.f;
+    for (int c = 0; c < nchunks; ++c) {
+      const size_t idx = (size_t)c * Ncap + k;
+      const float mc = part[idx];
+      if (mc == -__builtin_huge_valf()) continue;
+      const float w = __builtin_amdgcn_exp2f((mc - m) * kLog2e);
+      s = fmaf(part[plane + idx], w, s);
+      tt = fmaf(part[2 * plane + idx], w, tt);
+    }
+    o_lse = m + __builtin_amdgcn_logf(s) * kLn2;
+    o_lp = zy[k] - o_lse;
+    o_ent = o_lse - tt / s;
+  }
+  logp[i] = o_lp;
+  if (lse) lse[i] = o_lse;
+  if (ent) ent[i] = o_ent;
+}
+
+// ---- padded rows of dH -------------------------------------------------------------------
+
+// One wavefront per slot; only padded slots write.
+__global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ dH, int d,
+                                                        const int32_t* __restrict__ len, int R, int T) {
+  const int64_t N = (int64_t)R * T;
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  const int r = (int)(i / T);
+  const int t = (int)(i - (int64_t)r * T);
+  if (t < min(max(len[r], 0), T)) return;
+  typedef __attribute__((ext_vector_type(4))) float f4;
+  f4* row = reinterpret_cast<f4*>(dH + i * (int64_t)d);
+  const f4 z = {0.f, 0.f, 0.f, 0.f};
+  for (int c = threadIdx.x & 63; c < d / 4; c += 64) row[c] = z;
+}
+
+}  // namespace
+
+hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t* cu_ws,
+                        int32_t* row_slot, uint8_t* mask_out, int32_t* cu_out, hipStream_t s) {
+  hipLaunchKernelGGL(scan_len_kernel, dim3(1), dim3(1024), 0, s, len, R, T, hdr, cu_ws, cu_out);
+  const int64_t N = (int64_t)R * T;
+  const unsigned blocks = (unsigned)((N + kTile + 255) / 256);
+  hipLaunchKernelGGL(fill_index_kernel, dim3(blocks), dim3(256), 0, s, len, R, T, cu_ws, row_slot, mask_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
+                          const float* g, const float* lse, int64_t N, WsHeader* hdr,
+                          const int32_t* row_slot, void* Hc, int32_t* tok_c, float* g_c,
+                          float* lse_c, float* zy, hipStream_t s) {
+  const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
+  const int64_t cap = (N + kTile - 1) / kTile * kTile;
+  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)(cap / 4)), dim3(256), 0, s,
+                     static_cast<const char*>(H), ldH * esz, d * esz, V, tok, g, lse, hdr, row_slot,
+                     static_cast<char*>(Hc), tok_c, g ? g_c : nullptr, lse ? lse_c : nullptr, zy);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows_cap, int cols,
+                            bool rows_from_nv, const WsHeader* hdr, void* out, int64_t ld_out,
+                            int64_t cols_p, hipStream_t s) {
+  const dim3 grid((unsigned)((ld_out + 63) / 64), (unsigned)((cols_p + 63) / 64));
+  if (dtype == LMHEAD_BF16) {
+    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s,
+                       static_cast<const uint16_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
+                       hdr, static_cast<uint16_t*>(out), ld_out, cols_p);
+  } else {
+    hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s,
+                       static_cast<const uint32_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
+                       hdr, static_cast<uint32_t*>(out), ld_out, cols_p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int64_t Ncap,
+                           const int32_t* len, const int32_t* cu_len, int R, int T, float* logp,
+                           float* lse, float* entropy, hipStream_t s) {
+  const int64_t N = (int64_t)R * T;
+  hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, part, zy,
+                     nchunks, Ncap, len, cu_len, R, T, logp, lse, entropy);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_padded_rows(float* dH, int d, const int32_t* len, int R, int T, hipStream_t s) {
+  const int64_t N = (int64_t)R * T;
+  hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s, dH, d, len, R, T);
+  return hipGetLastError();
+}
+
+}  // namespace lmhead

@@ -1,0 +1,350 @@
+// The three MFMA kernels of the library, all built on GemmTile (gemm_core.h):
+//   fwd_kernel    logits tile (vocabulary x tokens) -> online max / sum-exp / sum-exp*z per token,
+//                 target-logit capture; nothing of the tile is stored           (log-softmax of L_CE, Eq. 9)
+//   dz_kernel     logits tile recomputed -> dZ = g (onehot - softmax), stored in both orientations
+//   gemm_t_kernel plain contraction with a transposed, row-mapped fp32 store    (dH and dW)
+//
+// Orientation: the vocabulary (or d) runs along the MFMA M axis and tokens (or vocabulary
+// rows of dW) along N.  With the 32x32 accumulator layout a lane then owns ONE token column
+// and 16*TM vocabulary entries of it, so the softmax statistics are reduced inside the lane
+// and need a single cross-lane step per chunk; and a lane's four consecutive M entries are
+// contiguous in the row-major outputs (dZ row, dH row, dW row).
+#include "common.h"
+#include "gemm_core.h"
+
+namespace lmhead {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegInf = -__builtin_huge_valf();
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename E>
+using Tile = GemmTile<E, 256, 256, 2, 2>;
+
+// Merge (m2, s2, t2) into (m, s, t): statistics of a union of disjoint logit sets.
+__device__ inline void merge_stats(float& m, float& s, float& t, float m2, float s2, float t2) {
+  const float mn = fmaxf(m, m2);
+  const float ms = (mn == kNegInf) ? 0.f : mn;
+  const float a = fast_exp2((m - ms) * kLog2e);
+  const float b = fast_exp2((m2 - ms) * kLog2e);
+  s = s * a + s2 * b;
+  t = t * a + t2 * b;
+  m = mn;
+}
+
+template <typename E>
+__global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
+  using G = Tile<E>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nv = a.hdr->nv;
+  const int nblk = (nv + G::BN - 1) / G::BN;
+  if ((int)blockIdx.x >= nblk) return;
+  const int64_t n0 = (int64_t)blockIdx.x * G::BN;
+  const int chunk = blockIdx.y;
+  const int total_tiles = (a.V + G::BM - 1) / G::BM;
+  const int t_lo = chunk * a.tiles_per_chunk;
+  const int t_hi = min(t_lo + a.tiles_per_chunk, total_tiles);
+  const int ksteps = a.d * Elem<E>::size / kKBytes;
+  const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
+  const int64_t pitchW = a.ldW * Elem<E>::size;
+  const char* Hc = static_cast<const char*>(a.Hc);
+  const char* W = static_cast<const char*>(a.W);
+
+  int64_t offB[G::B_CH];
+#pragma unroll
+  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchH + G::ld_chunk() * 16;
+
+  int tokj[G::TN];
+  float mr[G::TN], sr[G::TN], tr[G::TN];
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    tokj[j] = a.tok_c[n0 + G::n_of(j)];
+    mr[j] = kNegInf;
+    sr[j] = 0.f;
+    tr[j] = 0.f;
+  }
+
+  for (int tile = t_lo; tile < t_hi; ++tile) {
+    const int m0 = tile * G::BM;
+    int64_t offA[G::A_CH];
+#pragma unroll
+    for (int p = 0; p < G::A_CH; ++p)
+      offA[p] = (int64_t)min(m0 + G::ld_row(p), a.V - 1) * pitchW + G::ld_chunk() * 16;
+    typename G::Acc acc;
+    G::zero(acc);
+    G::run(acc, W, offA, Hc, offB, ksteps, smem);
+
+    // target-logit capture: only where some lane's target falls inside this tile
+    bool hit = false;
+#pragma unroll
+    for (int j = 0; j < G::TN; ++j) hit |= (tokj[j] >= m0) & (tokj[j] < m0 + G::BM);
+    if (__any(hit)) {
+#pragma unroll
+      for (int j = 0; j < G::TN; ++j) {
+        const int rel = tokj[j] - m0;
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (G::m_of(i, v) == rel) a.zy[n0 + G::n_of(j)] = acc[i][j][v];
+      }
+    }
+
+    // online softmax statistics, inside the lane
+    const bool full = m0 + G::BM <= a.V;
+#pragma unroll
+    for (int j = 0; j < G::TN; ++j) {
+      float tmax = kNegInf;
+      if (full) {
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, acc[i][j][v]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            tmax = fmaxf(tmax, (m0 + G::m_of(i, v) < a.V) ? acc[i][j][v] : kNegInf);
+      }
+      const float mn = fmaxf(mr[j], tmax);
+      const float ms = (mn == kNegInf) ? 0.f : mn;
+      const float sc = fast_exp2((mr[j] - ms) * kLog2e);
+      const float bias = -ms * kLog2e;
+      float ss = 0.f, ts = 0.f;
+      if (full) {
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float z = acc[i][j][v];
+            const float e = fast_exp2(fmaf(z, kLog2e, bias));
+            ss += e;
+            ts = fmaf(e, z, ts);
+          }
+      } else {
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const bool ok = m0 + G::m_of(i, v) < a.V;
+            const float z = ok ? acc[i][j][v] : 0.f;
+            const float e = ok ? fast_exp2(fmaf(z, kLog2e, bias)) : 0.f;
+            ss += e;
+            ts = fmaf(e, z, ts);
+          }
+      }
+      sr[j] = fmaf(sr[j], sc, ss);
+      tr[j] = fmaf(tr[j], sc, ts);
+      mr[j] = mn;
+    }
+  }
+
+  // combine the two half-waves (same token, other vocabulary rows), then the WGM waves via LDS
+  float* red = reinterpret_cast<float*>(smem);  // [WGM][BN][3]
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const float m2 = __shfl_xor(mr[j], 32);
+    const float s2 = __shfl_xor(sr[j], 32);
+    const float t2 = __shfl_xor(tr[j], 32);
+    merge_stats(mr[j], sr[j], tr[j], m2, s2, t2);
+    if (G::lane() < 32) {
+      float* q = red + ((size_t)G::wave_m() * G::BN + G::n_of(j)) * 3;
+      q[0] = mr[j];
+      q[1] = sr[j];
+      q[2] = tr[j];
+    }
+  }
+  __syncthreads();
+  for (int n = threadIdx.x; n < G::BN; n += G::NT) {
+    float m = red[n * 3], s = red[n * 3 + 1], t = red[n * 3 + 2];
+#pragma unroll
+    for (int w = 1; w < G::WGM; ++w) {
+      const float* q = red + ((size_t)w * G::BN + n) * 3;
+      merge_stats(m, s, t, q[0], q[1], q[2]);
+    }
+    const size_t base = (size_t)chunk * a.Ncap + n0 + n;
+    const size_t plane = (size_t)a.nchunks * a.Ncap;
+    a.part[base] = m;
+    a.part[plane + base] = s;
+    a.part[2 * plane + base] = t;
+  }
+}
+
+template <typename E>
+struct Store4;
+template <>
+struct Store4<bf16_tag> {
+  __device__ static inline void row(void* p, float a, float b, float c, float d) {
+    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+    bf16x4_t v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    *reinterpret_cast<bf16x4_t*>(p) = v;
+  }
+  __device__ static inline void one(void* p, float a) { *reinterpret_cast<__bf16*>(p) = (__bf16)a; }
+};
+template <>
+struct Store4<f32_tag> {
+  __device__ static inline void row(void* p, float a, float b, float c, float d) {
+    f32x4_t v = {a, b, c, d};
+    *reinterpret_cast<f32x4_t*>(p) = v;
+  }
+  __device__ static inline void one(void* p, float a) { *reinterpret_cast<float*>(p) = a; }
+};
+
+template <typename E>
+__global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
+  using G = Tile<E>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nv = a.hdr->nv;
+  const int nblk = (nv + G::BN - 1) / G::BN;
+  if ((int)blockIdx.x >= nblk) return;
+  const int64_t n0 = (int64_t)blockIdx.x * G::BN;
+  const int mrel0 = blockIdx.y * G::BM;  // within the chunk
+  const int m0 = a.c0 + mrel0;
+  const int ksteps = a.d * Elem<E>::size / kKBytes;
+  const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
+  const int64_t pitchW = a.ldW * Elem<E>::size;
+
+  int64_t offA[G::A_CH], offB[G::B_CH];
+#pragma unroll
+  for (int p = 0; p < G::A_CH; ++p)
+    offA[p] = (int64_t)min(m0 + G::ld_row(p), a.V - 1) * pitchW + G::ld_chunk() * 16;
+#pragma unroll
+  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchH + G::ld_chunk() * 16;
+
+  typename G::Acc acc;
+  G::zero(acc);
+  G::run(acc, static_cast<const char*>(a.W), offA, static_cast<const char*>(a.Hc), offB, ksteps, smem);
+
+  char* dZ = static_cast<char*>(a.dZ);
+  char* dZT = static_cast<char*>(a.dZT);
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const int64_t n = n0 + G::n_of(j);
+    const float g = a.g_c[n];
+    const float bias = -a.lse_c[n] * kLog2e;
+    const int rel = a.tok_c[n] - m0;
+#pragma unroll
+    for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float dz[4];
+        const int mt = G::m_of(i, 4 * q);  // tile-relative, multiple of 4
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kLog2e, bias));
+          const float oh = (mt + e == rel) ? 1.f : 0.f;
+          dz[e] = (m0 + mt + e < a.V) ? g * (oh - p) : 0.f;
+        }
+        const int64_t mc = mrel0 + mt;
+        Store4<E>::row(dZ + ((size_t)n * a.Vc + mc) * Elem<E>::size, dz[0], dz[1], dz[2], dz[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          Store4<E>::one(dZT + ((size_t)(mc + e) * a.Ncap + n) * Elem<E>::size, dz[e]);
+      }
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
+  using G = Tile<E>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nv = a.hdr->nv;
+  const int64_t n_lim = a.n_from_nv ? (int64_t)nv : a.n_limit;
+  const int64_t n0 = (int64_t)blockIdx.y * G::BN;
+  if (n0 >= n_lim) return;
+  const int m0 = blockIdx.x * G::BM;
+  const int64_t kel = a.k_from_nv ? (int64_t)nv : a.K;
+  const int ksteps = (int)((kel * Elem<E>::size + kKBytes - 1) / kKBytes);
+  const int64_t pitchA = a.ldA * Elem<E>::size;
+  const int64_t pitchB = a.ldB * Elem<E>::size;
+
+  int64_t offA[G::A_CH], offB[G::B_CH];
+#pragma unroll
+  for (int p = 0; p < G::A_CH; ++p) offA[p] = (int64_t)(m0 + G::ld_row(p)) * pitchA + G::ld_chunk() * 16;
+#pragma unroll
+  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchB + G::ld_chunk() * 16;
+
+  typename G::Acc acc;
+  G::zero(acc);
+  G::run(acc, static_cast<const char*>(a.A), offA, static_cast<const char*>(a.B), offB, ksteps, smem);
+
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const int64_t n = n0 + G::n_of(j);
+    if (n >= n_lim) continue;
+    const int64_t row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
+    if (row < 0) continue;
+    float* orow = a.out + row * a.ldo;
+#pragma unroll
+    for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int m = m0 + G::m_of(i, 4 * q);
+        if (m >= a.M) continue;
+        f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        f32x4_t* dst = reinterpret_cast<f32x4_t*>(orow + m);
+        if (a.accumulate) v += *dst;
+        *dst = v;
+      }
+  }
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s) {
+  const dim3 grid((unsigned)(a.Ncap / kTile), (unsigned)a.nchunks);
+  hipError_t e;
+  if (dtype == LMHEAD_BF16) {
+    using G = Tile<bf16_tag>;
+    if ((e = allow_lds(fwd_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(fwd_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  } else {
+    using G = Tile<f32_tag>;
+    if ((e = allow_lds(fwd_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(fwd_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s) {
+  const dim3 grid((unsigned)(a.Ncap / kTile), (unsigned)a.ntiles);
+  hipError_t e;
+  if (dtype == LMHEAD_BF16) {
+    using G = Tile<bf16_tag>;
+    if ((e = allow_lds(dz_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(dz_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  } else {
+    using G = Tile<f32_tag>;
+    if ((e = allow_lds(dz_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(dz_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s) {
+  const dim3 grid((unsigned)((a.M + kTile - 1) / kTile), (unsigned)a.n_tiles_cap);
+  hipError_t e;
+  if (dtype == LMHEAD_BF16) {
+    using G = Tile<bf16_tag>;
+    if ((e = allow_lds(gemm_t_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_t_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  } else {
+    using G = Tile<f32_tag>;
+    if ((e = allow_lds(gemm_t_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_t_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lmhead

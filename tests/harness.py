@@ -1,0 +1,105 @@
+"""Test-side plumbing: upload seeded inputs, run the HIP path through the C ABI, run the oracle chain."""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as wl
+
+
+def to_device(a: np.ndarray):
+    """numpy -> torch device tensor; uint16 arrays are bf16 bit patterns."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+class GpuProblem:
+    """Device-resident tensors of one workload plus its workspace."""
+
+    def __init__(self, cfg, H, W, tok, lens, vocab_chunk=0, flags=0):
+        import torch
+        import paper_2603_04411_amd as L
+        self.L = L
+        self.cfg = cfg
+        self.desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=vocab_chunk, flags=flags)
+        assert L.validate_desc(self.desc) == 0
+        self.H = to_device(H)
+        self.W = to_device(W)
+        self.tok = to_device(np.ascontiguousarray(tok, dtype=np.int32))
+        self.lens = to_device(np.ascontiguousarray(lens, dtype=np.int32))
+        self.ws = torch.empty(L.workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
+        self.loss_ws = torch.empty(L.loss_workspace_bytes(cfg.P, cfg.G, cfg.T), dtype=torch.uint8, device="cuda")
+
+    def fwd(self, W=None, want_entropy=True, want_index=True):
+        import torch
+        cfg = self.cfg
+        N, R = cfg.N, cfg.R
+        f = dict(dtype=torch.float32, device="cuda")
+        logp = torch.full((N,), 7.0, **f)
+        lse = torch.full((N,), 7.0, **f)
+        ent = torch.full((N,), 7.0, **f) if want_entropy else None
+        mask = torch.full((N,), 9, dtype=torch.uint8, device="cuda") if want_index else None
+        cu = torch.full((R + 1,), -9, dtype=torch.int32, device="cuda") if want_index else None
+        self.L.lmhead_logprob_fwd(self.desc, self.H, self.W if W is None else W, self.tok, self.lens,
+                                  logp, lse, ent, mask, cu, self.ws)
+        return logp, lse, ent, mask, cu
+
+    def bwd(self, lse, g_logp, dW_init=None):
+        import torch
+        cfg = self.cfg
+        dH = torch.full((cfg.N, cfg.d), 3.0, dtype=torch.float32, device="cuda")
+        dW = torch.full((cfg.V, cfg.d), 3.0, dtype=torch.float32, device="cuda") if dW_init is None else dW_init
+        self.L.lmhead_logprob_bwd(self.desc, self.H, self.W, self.tok, self.lens, lse, g_logp, dH, dW, self.ws)
+        return dH, dW
+
+    def advantage(self, rewards, eps=1e-6, ddof=0):
+        import torch
+        r = to_device(np.ascontiguousarray(rewards, dtype=np.float32))
+        adv = torch.empty_like(r)
+        self.L.group_advantage(r, self.cfg.P, self.cfg.G, eps, ddof, adv)
+        return adv
+
+    def grpo(self, logp, logp_old, logp_ref, adv, clip_lo=0.2, clip_hi=0.2, kl=0.04, agg=0):
+        import torch
+        cfg = self.cfg
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        g = torch.full((cfg.N,), 5.0, dtype=torch.float32, device="cuda")
+        stats = torch.zeros(4, dtype=torch.float32, device="cuda")
+        self.L.grpo_loss(logp, logp_old, logp_ref, adv, self.lens, cfg.P, cfg.G, cfg.T, clip_lo, clip_hi, kl, agg,
+                         loss, g, stats, self.loss_ws)
+        return loss, g, stats
+
+    def flowrl(self, logp, logp_ref, rewards, logZ, beta):
+        import torch
+        cfg = self.cfg
+        r = to_device(np.ascontiguousarray(rewards, dtype=np.float32))
+        z = to_device(np.ascontiguousarray(logZ, dtype=np.float32))
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        g = torch.full((cfg.N,), 5.0, dtype=torch.float32, device="cuda")
+        gz = torch.zeros(cfg.P, dtype=torch.float32, device="cuda")
+        resid = torch.zeros(cfg.R, dtype=torch.float32, device="cuda")
+        self.L.flowrl_tb_loss(logp, logp_ref, r, z, self.lens, cfg.P, cfg.G, cfg.T, beta, loss, g, gz, resid,
+                              self.loss_ws)
+        return loss, g, gz, resid
+
+    def check(self):
+        return self.L.lmhead_check(self.ws)
+
+
+def np64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_fro(a, b):
+    """||a - b||_F / ||b||_F."""
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+
+
+def small_inputs(cfg):
+    """All inputs of a (small) workload as numpy arrays."""
+    return dict(
+        H=wl.hidden(cfg), W=wl.weight(cfg), W_old=wl.weight(cfg, "old"), W_ref=wl.weight(cfg, "ref"),
+        tok=wl.tokens(cfg), lens=wl.lengths(cfg), rewards=wl.rewards(cfg), logZ=wl.log_z(cfg),
+    )

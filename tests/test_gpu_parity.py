@@ -1,0 +1,174 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Tolerances are the benchmark's: integers bit-exact; |dlogp| <= 1e-2; loss relative
+error <= 1e-3 (relative to max(|L|, sum w|l|) when L is near zero); relative
+Frobenius error of dH and dW <= 1e-2.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lmhead_oracle as O
+from tests.harness import GpuProblem, np64, rel_fro, small_inputs, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL_LOGP = 1e-2
+TOL_LOSS = 1e-3
+TOL_GRAD = 1e-2
+
+
+def _fwd_parity(cfg, inp, W_key="W", vocab_chunk=0):
+    gp = GpuProblem(cfg, inp["H"], inp[W_key], inp["tok"], inp["lens"], vocab_chunk=vocab_chunk)
+    logp, lse, ent, mask, cu = gp.fwd()
+    assert gp.check() == 0
+    o_mask, o_cu, o_rs, _ = O.index_build(inp["lens"], cfg.T)
+    assert np.array_equal(mask.cpu().numpy(), o_mask)
+    assert np.array_equal(cu.cpu().numpy(), o_cu)
+    o_lp, o_lse, o_ent = O.lmhead_logprob_fwd(wl.as_f64(inp["H"]), wl.as_f64(inp[W_key]), inp["tok"], inp["lens"], cfg.T)
+    for got, want, name in ((logp, o_lp, "logp"), (lse, o_lse, "lse"), (ent, o_ent, "entropy")):
+        g = np64(got)
+        assert np.all(g[o_mask == 0] == 0), f"{name}: padded slots must be exactly 0"
+        err = np.abs(g - want).max()
+        assert err <= TOL_LOGP, f"{name}: max abs err {err}"
+    return gp, (logp, lse, ent), (o_lp, o_lse, o_ent)
+
+
+def _grpo_chain(cfg, inp, vocab_chunk=0, W_old_key="W_old"):
+    """fwd(theta, old, ref) -> advantages -> GRPO loss -> bwd, on GPU and in the oracle."""
+    gp, (logp, lse, ent), (o_lp, o_lse, o_ent) = _fwd_parity(cfg, inp, vocab_chunk=vocab_chunk)
+    lp_old, *_ = gp.fwd(W=to_device(inp[W_old_key]), want_entropy=False, want_index=False)
+    lp_ref, *_ = gp.fwd(W=to_device(inp["W_ref"]), want_entropy=False, want_index=False)
+    adv = gp.advantage(inp["rewards"])
+    loss, g, stats = gp.grpo(logp, lp_old, lp_ref, adv, cfg.clip_eps, cfg.clip_eps, cfg.kl_coef, 0)
+    dH, dW = gp.bwd(lse, g)
+    assert gp.check() == 0
+
+    H64, T = wl.as_f64(inp["H"]), cfg.T
+    o_old, _, _ = O.lmhead_logprob_fwd(H64, wl.as_f64(inp[W_old_key]), inp["tok"], inp["lens"], T)
+    o_ref, _, _ = O.lmhead_logprob_fwd(H64, wl.as_f64(inp["W_ref"]), inp["tok"], inp["lens"], T)
+    o_adv = O.group_advantage(inp["rewards"], cfg.P, cfg.G, 1e-6, 0)
+    args = (o_lp, o_old, o_ref, o_adv, inp["lens"], cfg.P, cfg.G, T, cfg.clip_eps, cfg.clip_eps, cfg.kl_coef, 0)
+    o_loss, o_g, o_stats = O.grpo_loss(*args)
+    scale = max(abs(o_loss), O.grpo_abs_scale(*args))
+    o_dH, o_dW = O.lmhead_logprob_bwd(H64, wl.as_f64(inp["W"]), inp["tok"], inp["lens"], T, o_g)
+
+    assert np.abs(np64(adv) - o_adv).max() <= 1e-4
+    assert abs(float(loss.item()) - o_loss) <= TOL_LOSS * scale, (float(loss.item()), o_loss, scale)
+    mask = O.index_build(inp["lens"], T)[0]
+    gh = np64(dH)
+    assert np.all(gh[mask == 0] == 0), "padded rows of dH must be exactly 0"
+    e_h, e_w = rel_fro(gh, o_dH), rel_fro(np64(dW), o_dW)
+    assert e_h <= TOL_GRAD and e_w <= TOL_GRAD, (e_h, e_w)
+    return dict(err_dH=e_h, err_dW=e_w, stats=np64(stats), o_stats=o_stats)
+
+
+def test_config0_fp32_grpo_end_to_end():
+    cfg = wl.CONFIGS[0]
+    r = _grpo_chain(cfg, small_inputs(cfg))
+    assert r["err_dH"] < 1e-4 and r["err_dW"] < 1e-4     # fp32 path: far inside the bf16 tolerances
+    assert abs(r["stats"][3] - r["o_stats"][3]) == 0     # N_v
+    assert np.abs(r["stats"][:3] - r["o_stats"][:3]).max() < 1e-3
+
+
+def test_config0_fp32_flowrl():
+    cfg = wl.CONFIGS[0]
+    inp = small_inputs(cfg)
+    gp, (logp, lse, ent), (o_lp, o_lse, o_ent) = _fwd_parity(cfg, inp)
+    lp_ref, *_ = gp.fwd(W=to_device(inp["W_ref"]), want_entropy=False, want_index=False)
+    o_ref, _, _ = O.lmhead_logprob_fwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W_ref"]), inp["tok"], inp["lens"], cfg.T)
+    loss, g, gz, resid = gp.flowrl(logp, lp_ref, inp["rewards"], inp["logZ"], 1.0)
+    o_loss, o_g, o_gz, o_resid = O.flowrl_tb_loss(o_lp, o_ref, inp["rewards"], inp["logZ"], inp["lens"],
+                                                  cfg.P, cfg.G, cfg.T, 1.0)
+    assert abs(float(loss.item()) - o_loss) <= TOL_LOSS * abs(o_loss)
+    assert np.abs(np64(resid) - o_resid).max() <= 1e-3
+    assert rel_fro(np64(gz), o_gz) <= 1e-3 and rel_fro(np64(g), o_g) <= 1e-3
+    dH, dW = gp.bwd(lse, g)
+    o_dH, o_dW = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, o_g)
+    assert rel_fro(np64(dH), o_dH) <= TOL_GRAD and rel_fro(np64(dW), o_dW) <= TOL_GRAD
+
+
+@pytest.mark.parametrize("vocab_chunk", [0, 2048])
+def test_bf16_small_grpo_several_tiles_and_ragged_tails(vocab_chunk):
+    # config 1's distributions at a size the oracle finishes in seconds: N_v spans two token tiles with a
+    # ragged tail, V spans 33 vocabulary tiles with a ragged last tile and (chunk 2048) five chunks
+    cfg = wl.CONFIGS[1].scaled(P=2, G=4, T=96, d=256, V=8192 + 100)
+    _grpo_chain(cfg, small_inputs(cfg), vocab_chunk=vocab_chunk)
+
+
+def test_bf16_small_near_policy_unclipped_branch():
+    cfg = wl.CONFIGS[1].scaled(P=2, G=4, T=64, d=128, V=3000)
+    inp = small_inputs(cfg)
+    inp["W_near"] = wl.perturbed_weight(cfg, inp["W"])
+    r = _grpo_chain(cfg, inp, W_old_key="W_near")
+    assert r["o_stats"][0] < 0.5     # most tokens are on the unclipped branch here
+
+
+def test_bf16_small_flowrl_loguniform_lengths():
+    cfg = wl.CONFIGS[3].scaled(P=3, G=4, T=128, d=192, V=5000, len_lo=1, len_hi=128)
+    inp = small_inputs(cfg)
+    gp, (logp, lse, ent), (o_lp, o_lse, o_ent) = _fwd_parity(cfg, inp)
+    lp_ref, *_ = gp.fwd(W=to_device(inp["W_ref"]), want_entropy=False, want_index=False)
+    o_ref, _, _ = O.lmhead_logprob_fwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W_ref"]), inp["tok"], inp["lens"], cfg.T)
+    loss, g, gz, resid = gp.flowrl(logp, lp_ref, inp["rewards"], inp["logZ"], cfg.beta)
+    o_loss, o_g, o_gz, o_resid = O.flowrl_tb_loss(o_lp, o_ref, inp["rewards"], inp["logZ"], inp["lens"],
+                                                  cfg.P, cfg.G, cfg.T, cfg.beta)
+    assert abs(float(loss.item()) - o_loss) <= TOL_LOSS * abs(o_loss)
+    dH, dW = gp.bwd(lse, g)
+    o_dH, o_dW = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, o_g)
+    assert rel_fro(np64(dH), o_dH) <= TOL_GRAD and rel_fro(np64(dW), o_dW) <= TOL_GRAD
+
+
+def test_edge_lengths_zero_full_and_empty_batch():
+    import torch
+    cfg = wl.CONFIGS[1].scaled(P=2, G=2, T=40, d=64, V=700)
+    inp = small_inputs(cfg)
+    for lens in ([0, 40, 1, 0], [40, 40, 40, 40], [0, 0, 0, 0]):
+        inp["lens"] = np.array(lens, dtype=np.int32)
+        gp, (logp, lse, ent), (o_lp, _, _) = _fwd_parity(cfg, inp)
+        o_g = np.where(O.index_build(inp["lens"], cfg.T)[0] == 1, 0.01, 0.0)
+        dH, dW = gp.bwd(lse, to_device(o_g.astype(np.float32)))
+        o_dH, o_dW = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, o_g)
+        if sum(lens) == 0:
+            assert torch.count_nonzero(dH) == 0 and torch.count_nonzero(dW) == 0
+        else:
+            assert rel_fro(np64(dH), o_dH) <= TOL_GRAD and rel_fro(np64(dW), o_dW) <= TOL_GRAD
+
+
+def test_device_side_range_errors_are_reported():
+    cfg = wl.CONFIGS[1].scaled(P=1, G=2, T=16, d=64, V=300)
+    inp = small_inputs(cfg)
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"])
+    gp.fwd()
+    assert gp.check() == 0
+    bad_tok = inp["tok"].copy()
+    bad_tok[0] = cfg.V          # slot 0 is valid (every length >= 1 here)
+    gp2 = GpuProblem(cfg, inp["H"], inp["W"], bad_tok, inp["lens"])
+    gp2.fwd()
+    assert gp2.check() == -6
+    pad_tok = inp["tok"].copy()
+    pad_tok[cfg.T - 1] = -5     # padded slot: ignored
+    lens = inp["lens"].copy(); lens[0] = cfg.T - 1
+    gp3 = GpuProblem(cfg, inp["H"], inp["W"], pad_tok, lens)
+    gp3.fwd()
+    assert gp3.check() == 0
+    gp4 = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], np.array([cfg.T + 1, 3], dtype=np.int32))
+    gp4.fwd()
+    assert gp4.check() == -6
+
+
+def test_accumulate_dw_flag_and_reproducibility():
+    import torch
+    from paper_2603_04411_amd.binding import FLAG_ACCUM_DW
+    cfg = wl.CONFIGS[1].scaled(P=1, G=4, T=80, d=128, V=1500)
+    inp = small_inputs(cfg)
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"])
+    logp, lse, *_ = gp.fwd()
+    g = to_device(np.where(O.index_build(inp["lens"], cfg.T)[0] == 1, -0.003, 0.0).astype(np.float32))
+    dH1, dW1 = gp.bwd(lse, g)
+    dH2, dW2 = gp.bwd(lse, g)
+    assert torch.equal(dH1, dH2) and torch.equal(dW1, dW2)      # no float atomics: bit-reproducible
+    gp_acc = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"], flags=FLAG_ACCUM_DW)
+    base = torch.full((cfg.V, cfg.d), 0.5, dtype=torch.float32, device="cuda")
+    _, dW3 = gp_acc.bwd(lse, g, dW_init=base.clone())
+    assert torch.allclose(dW3, dW1 + 0.5, atol=1e-6)
