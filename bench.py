@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LM-head log-prob + policy-loss step (forward + backward) on one MI355X.
+
+One step = one pass of the whole hot path over one batch of seeded synthetic input, all
+tensors already resident in HBM:
+    lmhead_logprob_fwd(theta) [+ fwd(old), fwd(ref) where the workload recomputes them]
+    -> group_advantage -> grpo_loss | flowrl_tb_loss -> lmhead_logprob_bwd (dH, dW).
+Prints ONE JSON line (metric: valid tokens/s of the step) with a `roofline` object for the
+dominant matrix-core kernel (timed with HIP events inside the library, on the launch stream)
+and a `cpu_baseline` object (the fp64 oracle timed on the host cores on a bounded row sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3
+KERNEL_NAMES = ["fwd_kernel (logits + online softmax)", "dz_kernel (logits recompute -> dZ)",
+                "gemm_t_kernel<dH>", "gemm_t_kernel<dW>"]
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def to_device(a: np.ndarray):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def cpu_baseline(cfg, H_host, W_host, tok, lens, sample_rows: int, gpu_logp=None):
+    """Times the oracle (as it stands) on a seeded subset of valid rows: fwd + CE-style bwd."""
+    import workloads as wl
+    from oracle import lmhead_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rows = wl.sample_valid_rows(cfg, lens, tok, sample_rows)
+    Hs = wl.as_f64(H_host[rows])
+    W64 = wl.as_f64(W_host)
+    t0 = time.perf_counter()
+    lp, lse, ent = O.logprob_rows(Hs, W64, tok[rows])
+    g = np.full(rows.size, -1.0 / rows.size)
+    dH, dW = O.bwd_rows(Hs, W64, tok[rows], g)
+    dt = time.perf_counter() - t0
+    out = {"value": rows.size / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{rows.size} seeded valid rows of the same workload, full V and d: "
+                     f"fp64 logits+lse+entropy forward, then dZ, dH rows and the rows' dW ({dt:.1f} s)"}
+    if gpu_logp is not None:
+        out["gpu_vs_oracle_max_abs_logp_err_on_sample"] = float(np.abs(gpu_logp[rows] - lp).max())
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the target config)")
+    ap.add_argument("--vocab-chunk", type=int, default=0)
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of the oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as wl
+    import paper_2603_04411_amd as L
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    cfg = wl.CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    f32 = dict(dtype=torch.float32, device="cuda")
+
+    t_gen = time.perf_counter()
+    log(f"generating workload {cfg.name}: N={cfg.N} d={cfg.d} V={cfg.V} ({cfg.dtype})")
+    lens, tok = wl.lengths(cfg), wl.tokens(cfg)
+    rewards, logZ = wl.rewards(cfg), wl.log_z(cfg)
+    H_host = wl.hidden(cfg)
+    log(f"H done ({time.perf_counter() - t_gen:.1f} s)")
+    W_host = wl.weight(cfg)
+    H, W = to_device(H_host), to_device(W_host)
+    W_old = to_device(wl.weight(cfg, "old")) if cfg.loss == "grpo" else None
+    W_ref = to_device(wl.weight(cfg, "ref"))
+    log(f"weights done ({time.perf_counter() - t_gen:.1f} s)")
+    tok_d, lens_d = to_device(tok), to_device(lens)
+    rew_d, logZ_d = to_device(rewards), to_device(logZ)
+    nv = int(lens.sum())
+
+    desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=args.vocab_chunk)
+    assert L.validate_desc(desc) == 0
+    ws = torch.empty(L.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    loss_ws = torch.empty(L.loss_workspace_bytes(cfg.P, cfg.G, cfg.T), dtype=torch.uint8, device="cuda")
+    N = cfg.N
+    logp, lse = torch.empty(N, **f32), torch.empty(N, **f32)
+    ent = torch.empty(N, **f32) if cfg.want_entropy else None
+    lp_old, lp_ref = torch.empty(N, **f32), torch.empty(N, **f32)
+    scratch_lse = torch.empty(N, **f32)
+    adv = torch.empty(cfg.R, **f32)
+    loss = torch.zeros(1, **f32)
+    g_logp = torch.empty(N, **f32)
+    g_logZ = torch.empty(cfg.P, **f32)
+    stats = torch.zeros(4, **f32)
+    dH = torch.empty(N, cfg.d, **f32)
+    dW = torch.empty(cfg.V, cfg.d, **f32)
+
+    def fwd_other():
+        if W_old is not None:
+            L.lmhead_logprob_fwd(desc, H, W_old, tok_d, lens_d, lp_old, scratch_lse, None, None, None, ws)
+        L.lmhead_logprob_fwd(desc, H, W_ref, tok_d, lens_d, lp_ref, scratch_lse, None, None, None, ws)
+
+    def step():
+        L.lmhead_logprob_fwd(desc, H, W, tok_d, lens_d, logp, lse, ent, None, None, ws)
+        if cfg.recompute_old_ref:
+            fwd_other()
+        if cfg.loss == "grpo":
+            L.group_advantage(rew_d, cfg.P, cfg.G, 1e-6, 0, adv)
+            L.grpo_loss(logp, lp_old, lp_ref, adv, lens_d, cfg.P, cfg.G, cfg.T, cfg.clip_eps, cfg.clip_eps,
+                        cfg.kl_coef, 0, loss, g_logp, stats, loss_ws)
+        else:
+            L.flowrl_tb_loss(logp, lp_ref, rew_d, logZ_d, lens_d, cfg.P, cfg.G, cfg.T, cfg.beta, loss, g_logp,
+                             g_logZ, None, loss_ws)
+        L.lmhead_logprob_bwd(desc, H, W, tok_d, lens_d, lse, g_logp, dH, dW, ws)
+
+    if not cfg.recompute_old_ref:
+        fwd_other()      # old / reference log-probs are inputs of the step here: computed once, untimed
+    torch.cuda.synchronize()
+    log(f"setup done ({time.perf_counter() - t_gen:.1f} s); warmup x{args.warmup}")
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if L.lmhead_check(ws) != 0:
+        print("bench.py: device-side range error in the synthetic inputs", file=sys.stderr)
+        return 4
+
+    L.lmhead_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = [L.lmhead_timing_read(k) for k in range(4)]
+    L.lmhead_timing_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    log(f"{ms_per_step:.1f} ms/step, loss {float(loss.item()):.6f}")
+
+    # roofline of the dominant matrix-core kernel: algorithmic flops per launch = 2 * N_v * d * (vocabulary
+    # columns the launch covers); summed over a pass that is 2 * N_v * V * d per kernel kind.
+    n_fwd_passes = 1 + ((2 if W_old is not None else 1) if cfg.recompute_old_ref else 0)
+    flops_per_pass = 2.0 * nv * cfg.V * cfg.d
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
+    kinds = []
+    for k, (ms, n) in enumerate(kern):
+        passes = args.steps * (n_fwd_passes if k == 0 else 1)
+        tf = flops_per_pass * passes / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        kinds.append({"kernel": KERNEL_NAMES[k], "launches": int(n), "avg_ms": ms / n if n else 0.0,
+                      "total_ms": ms, "tflops": tf, "frac": tf / peak})
+    dom = max(range(4), key=lambda k: kern[k][0])
+    dms, dn = kern[dom]
+    dom_passes = args.steps * (n_fwd_passes if dom == 0 else 1)
+    flops_per_launch = flops_per_pass * dom_passes / dn
+    achieved = flops_per_launch / (dms / dn * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom], "achieved": achieved, "peak": peak,
+                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "flops_per_launch": flops_per_launch, "avg_launch_ms": dms / dn}
+    step_flops_hw = flops_per_pass * (3 + n_fwd_passes)       # executed, including the dZ recompute
+    step_flops_model = flops_per_pass * 3                      # logits + dH + dW
+
+    gpu_logp = logp.double().cpu().numpy()
+    cpu = None
+    if args.cpu_rows > 0:
+        log(f"timing the oracle on {args.cpu_rows} rows")
+        cpu = cpu_baseline(cfg, H_host, W_host, tok, lens, args.cpu_rows, gpu_logp)
+
+    out = {
+        "metric": "tokens/s fused LM-head logprob+loss fwd+bwd (1 GPU)",
+        "value": nv / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}", "P": cfg.P, "G": cfg.G, "T": cfg.T,
+                   "d": cfg.d, "V": cfg.V, "token_slots": cfg.N, "valid_tokens": nv, "loss": cfg.loss,
+                   "vocab_chunk": int(args.vocab_chunk) or 8192,
+                   "tokens_counted": "valid (unpadded) tokens", "slots_per_s": cfg.N / (ms_per_step * 1e-3)},
+        "step_tflops_executed": step_flops_hw / (ms_per_step * 1e-3) / 1e12,
+        "step_frac_of_peak_executed": step_flops_hw / (ms_per_step * 1e-3) / 1e12 / peak,
+        "step_tflops_model": step_flops_model / (ms_per_step * 1e-3) / 1e12,
+        "loss": float(loss.item()),
+        "roofline": roofline,
+        "kernels": kinds,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -181,6 +181,18 @@ LMHEAD_API int flowrl_tb_loss(const float* logp, const float* logp_ref, const fl
  */
 LMHEAD_API int lmhead_check(void* ws, void* stream);
 
+/*
+ * Optional instrumentation for benchmarks (the only process-wide state of the library; not
+ * thread-safe).  lmhead_timing_enable(1) makes lmhead_logprob_fwd/bwd bracket each of their
+ * matrix-core kernel launches with two HIP events on the launch stream (a fixed pool of 8192
+ * pairs; launches beyond it are not timed) and clears earlier records; (0) turns it off.
+ * lmhead_timing_read waits for the recorded events and returns, for one kernel kind
+ * (0 = logits forward, 1 = dZ recompute, 2 = dH contraction, 3 = dW contraction), the summed
+ * elapsed milliseconds and the number of launches since the last enable call.
+ */
+LMHEAD_API int lmhead_timing_enable(int on);
+LMHEAD_API int lmhead_timing_read(int kind, double* total_ms, int64_t* launches);
+
 /* Version of this ABI (bumped on any incompatible change). */
 LMHEAD_API int lmhead_abi_version(void);
 

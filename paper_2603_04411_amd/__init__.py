@@ -20,6 +20,8 @@ from .binding import (
     grpo_loss,
     flowrl_tb_loss,
     lmhead_check,
+    lmhead_timing_enable,
+    lmhead_timing_read,
     EXPORTED_SYMBOLS,
 )
 
@@ -27,5 +29,5 @@ __all__ = [
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
-    "flowrl_tb_loss", "lmhead_check", "EXPORTED_SYMBOLS",
+    "flowrl_tb_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
 ]

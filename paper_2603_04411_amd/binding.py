@@ -17,6 +17,7 @@ EXPORTED_SYMBOLS = [
     "lmhead_abi_version", "lmhead_workspace_bytes", "lmhead_validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage",
     "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "lmhead_check",
+    "lmhead_timing_enable", "lmhead_timing_read",
 ]
 
 ERRORS = {
@@ -84,6 +85,10 @@ def load_library():
     lib.flowrl_tb_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.lmhead_check.restype = C.c_int
     lib.lmhead_check.argtypes = [vp, vp]
+    lib.lmhead_timing_enable.restype = C.c_int
+    lib.lmhead_timing_enable.argtypes = [C.c_int]
+    lib.lmhead_timing_read.restype = C.c_int
+    lib.lmhead_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -161,3 +166,14 @@ def flowrl_tb_loss(logp, logp_ref, reward, logZ, lens, P, G, T, beta, loss, g_lo
 def lmhead_check(ws) -> int:
     """Synchronises the current stream; returns 0 or the (negative) sticky device status."""
     return int(load_library().lmhead_check(_ptr(ws), _stream()))
+
+
+def lmhead_timing_enable(on: bool) -> None:
+    _check(load_library().lmhead_timing_enable(1 if on else 0), "lmhead_timing_enable")
+
+
+def lmhead_timing_read(kind: int):
+    """(total milliseconds, launches) of one kernel kind since timing was enabled."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(load_library().lmhead_timing_read(kind, C.byref(ms), C.byref(n)), "lmhead_timing_read")
+    return ms.value, n.value

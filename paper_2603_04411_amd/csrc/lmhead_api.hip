@@ -32,6 +32,35 @@ struct Ws {
   T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
 };
 
+// ---- optional per-kernel timing -------------------------------------------------------
+// When enabled, each MFMA kernel launch is bracketed by two HIP events recorded on the launch
+// stream.  The pool is fixed-size; launches beyond it are simply not timed.
+constexpr int kTimingKinds = 4;  // 0 logits fwd, 1 dZ recompute, 2 dH, 3 dW
+constexpr int kTimingPool = 8192;
+struct TimingState {
+  bool on = false;
+  int used = 0;
+  hipEvent_t start[kTimingPool];
+  hipEvent_t stop[kTimingPool];
+  int kind[kTimingPool];
+  int created = 0;
+};
+TimingState g_timing;
+
+struct TimedLaunch {
+  hipStream_t s;
+  int slot = -1;
+  TimedLaunch(int kind, hipStream_t stream) : s(stream) {
+    if (!g_timing.on || g_timing.used >= g_timing.created) return;
+    slot = g_timing.used++;
+    g_timing.kind[slot] = kind;
+    (void)hipEventRecord(g_timing.start[slot], s);
+  }
+  ~TimedLaunch() {
+    if (slot >= 0) (void)hipEventRecord(g_timing.stop[slot], s);
+  }
+};
+
 #define LM_TRY(expr)                         \
   do {                                       \
     if ((expr) != hipSuccess) return LMHEAD_E_HIP; \
@@ -94,7 +123,10 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
   fa.hdr = hdr;
   fa.part = w.at<float>(L.part);
   fa.zy = w.at<float>(L.zy);
-  LM_TRY(launch_fwd(desc->dtype, fa, s));
+  {
+    TimedLaunch tl(0, s);
+    LM_TRY(launch_fwd(desc->dtype, fa, s));
+  }
   LM_TRY(launch_finalize(w.at<float>(L.part), w.at<float>(L.zy), (int)L.nchunks, L.Ncap, len,
                          w.at<int32_t>(L.cu_len), (int)L.R, desc->T, logp, lse, entropy, s));
   return LMHEAD_OK;
@@ -149,7 +181,10 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     za.hdr = hdr;
     za.dZ = w.at<void>(L.dZ);
     za.dZT = w.at<void>(L.dZT);
-    LM_TRY(launch_dz(dt, za, s));
+    {
+      TimedLaunch tl(1, s);
+      LM_TRY(launch_dz(dt, za, s));
+    }
 
     // dH[slot(n)][m] (+)= sum_v W^T[m][c0 + v] dZ[n][v]
     GemmTArgs ha{};
@@ -167,7 +202,10 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     ha.accumulate = c > 0;
     ha.n_tiles_cap = L.Ncap / kTile;
     ha.hdr = hdr;
-    LM_TRY(launch_gemm_t(dt, ha, s));
+    {
+      TimedLaunch tl(2, s);
+      LM_TRY(launch_gemm_t(dt, ha, s));
+    }
 
     // dW[c0 + n][m] = sum_i Hc^T[m][i] dZ^T[n][i]
     GemmTArgs wa{};
@@ -186,7 +224,10 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     wa.accumulate = (desc->flags & LMHEAD_FLAG_ACCUM_DW) != 0;
     wa.n_tiles_cap = ntiles;
     wa.hdr = hdr;
-    LM_TRY(launch_gemm_t(dt, wa, s));
+    {
+      TimedLaunch tl(3, s);
+      LM_TRY(launch_gemm_t(dt, wa, s));
+    }
   }
   return LMHEAD_OK;
 }
@@ -239,6 +280,37 @@ int lmhead_check(void* ws, void* stream) {
     return LMHEAD_E_HIP;
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return LMHEAD_E_HIP;
   return h.err != 0 ? LMHEAD_E_RANGE : LMHEAD_OK;
+}
+
+int lmhead_timing_enable(int on) {
+  if (on && g_timing.created == 0) {
+    for (int i = 0; i < kTimingPool; ++i) {
+      if (hipEventCreate(&g_timing.start[i]) != hipSuccess) return LMHEAD_E_HIP;
+      if (hipEventCreate(&g_timing.stop[i]) != hipSuccess) return LMHEAD_E_HIP;
+      g_timing.created = i + 1;
+    }
+  }
+  g_timing.on = on != 0;
+  g_timing.used = 0;
+  return LMHEAD_OK;
+}
+
+int lmhead_timing_read(int kind, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return LMHEAD_E_NULL;
+  if (kind < 0 || kind >= kTimingKinds) return LMHEAD_E_SHAPE;
+  double tot = 0.0;
+  int64_t cnt = 0;
+  for (int i = 0; i < g_timing.used; ++i) {
+    if (g_timing.kind[i] != kind) continue;
+    if (hipEventSynchronize(g_timing.stop[i]) != hipSuccess) return LMHEAD_E_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_timing.start[i], g_timing.stop[i]) != hipSuccess) return LMHEAD_E_HIP;
+    tot += ms;
+    ++cnt;
+  }
+  *total_ms = tot;
+  *launches = cnt;
+  return LMHEAD_OK;
 }
 
 }  // extern "C"

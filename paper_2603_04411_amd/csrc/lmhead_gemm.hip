@@ -249,7 +249,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   }
 }
 
-template <typename E>
+// Role: 0 = dH (contracts over a vocabulary chunk), 1 = dW (contracts over the valid tokens).  The
+// code is the same; the parameter only gives the two uses distinct kernel names in profiles.
+template <typename E, int Role>
 __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   using G = Tile<E>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -332,19 +334,21 @@ hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s) {
+template <typename E, int Role>
+static hipError_t launch_gemm_t_impl(const GemmTArgs& a, hipStream_t s) {
+  using G = Tile<E>;
   const dim3 grid((unsigned)((a.M + kTile - 1) / kTile), (unsigned)a.n_tiles_cap);
-  hipError_t e;
-  if (dtype == LMHEAD_BF16) {
-    using G = Tile<bf16_tag>;
-    if ((e = allow_lds(gemm_t_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_t_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  } else {
-    using G = Tile<f32_tag>;
-    if ((e = allow_lds(gemm_t_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_t_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  }
+  hipError_t e = allow_lds(gemm_t_kernel<E, Role>, G::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((gemm_t_kernel<E, Role>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();
+}
+
+hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s) {
+  const bool dw = a.k_from_nv;
+  if (dtype == LMHEAD_BF16)
+    return dw ? launch_gemm_t_impl<bf16_tag, 1>(a, s) : launch_gemm_t_impl<bf16_tag, 0>(a, s);
+  return dw ? launch_gemm_t_impl<f32_tag, 1>(a, s) : launch_gemm_t_impl<f32_tag, 0>(a, s);
 }
 
 }  // namespace lmhead
