@@ -10,9 +10,8 @@
 
 namespace lmhead {
 
-// Macro-tile of every contraction: 256 x 256 outputs, K consumed 128 bytes per row per step.
+// Macro-tile of every contraction: 256 x 256 outputs.
 constexpr int kTile = 256;
-constexpr int kKBytes = 128;
 
 // Sticky error bits written by kernels into WsHeader::err.
 constexpr int kErrLen = 1;  // a length outside [0, T]

@@ -3,19 +3,28 @@
 // All four contractions (logits, logits recompute for dZ, dH, dW) are brought to the
 // same form  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands K-contiguous.
 // A workgroup owns a BM x BN tile of C; each wavefront owns a (BM/WGM) x (BN/WGN)
-// sub-tile built from 32x32 MFMA blocks.  K is consumed 128 bytes per row per step
-// (64 bf16 or 32 fp32), staged through LDS in two alternating buffers while the next
-// step's global loads are in flight in registers.
+// sub-tile built from 32x32 MFMA blocks.
 //
-// LDS tile layout: row-major, 128 bytes (eight 16-byte chunks) per row, chunk c of
-// row r stored at chunk position c ^ (r & 7) so that the eight lanes served together
-// by a 128-bit LDS access touch all banks once, for the row-strided fragment reads as
-// well as for the row-contiguous tile writes.
+// Data movement: K is consumed 64 bytes per row per step (32 bf16 or 16 fp32).  Tiles go
+// from global memory straight into LDS (global_load_lds_dwordx4, no register staging)
+// through a ring of four stages, so three K-steps of loads are always in flight behind
+// the one being multiplied.  One workgroup barrier per K-step; completion of a stage is
+// tracked with the wave's own vmcnt (loads retire in order) followed by that barrier.
+//
+// LDS stage layout: A rows then B rows, 64 bytes (four 16-byte chunks) per row; chunk c
+// of row r sits at chunk position c ^ swz(r).  A direct-to-LDS load writes lane L's 16
+// bytes at wave_base + 16 L, i.e. row L/4, position L%4 of a 16-row group, so lane L
+// simply fetches the global chunk (L%4) ^ swz(row).  swz is chosen so that the 128-bit
+// fragment reads (32 consecutive rows, fixed chunk) are bank-conflict-free whether the
+// hardware serves 8 lanes over 32 banks or 16 lanes over 64 banks per cycle.
 //
 // Fragment layout used for both operands (what matters is only that A and B agree):
 // lane l of a 32-row block holds row l % 32 and the 16-byte chunk 2*s + l/32 of K
-// sub-step s.  For bf16 one v_mfma_f32_32x32x16_bf16 consumes the chunk; for fp32 the
-// chunk's four floats feed four v_mfma_f32_32x32x2_f32.
+// sub-step s (two sub-steps per K-step).  For bf16 one v_mfma_f32_32x32x16_bf16 consumes
+// the chunk; for fp32 the chunk's four floats feed four v_mfma_f32_32x32x2_f32.
+// Fragments are double-buffered in registers and the pipeline is skewed so that the
+// barrier falls between the two sub-steps: the MFMAs of sub-step 1 overlap the first
+// fragment reads of the next stage.
 //
 // Accumulator layout of a 32x32 block (16 floats per lane):
 //   element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4,  n = l % 32.
@@ -30,7 +39,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 struct bf16_tag {};
 struct f32_tag {};
@@ -61,33 +69,48 @@ struct Elem<f32_tag> {
   }
 };
 
+// s_waitcnt immediates (gfx9 encoding): only the named counter is constrained.
+constexpr int kWaitVm0 = 0x0F70;
+constexpr int kWaitVm16 = 0x4F70;
+constexpr int kWaitLgkm0 = 0xC07F;
+
 template <typename E, int BM_, int BN_, int WGM_, int WGN_>
 struct GemmTile {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
-  static constexpr int NT = 64 * WGM * WGN;
+  static constexpr int NWAVES = WGM * WGN;
+  static constexpr int NT = 64 * NWAVES;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 32, TN = WN / 32;
-  static constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;  // 16-byte chunks per thread
-  static constexpr int ROWS_PER_PASS = NT / 8;
-  static constexpr int STAGE = (BM + BN) * 128;
-  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int KB = 64;                       // bytes of K per row per step
+  static constexpr int NSTAGE = 4;
+  static constexpr int STAGE = (BM + BN) * KB;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int A_LD = BM / 16 / NWAVES;       // direct-to-LDS load instructions per wave
+  static constexpr int B_LD = BN / 16 / NWAVES;       // per K-step (each moves 16 rows)
+  static constexpr int LOADS_PER_STEP = A_LD + B_LD;
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tiles are 32x32 blocks");
-  static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "tile loads divide evenly");
+  static_assert(BM % (16 * NWAVES) == 0 && BN % (16 * NWAVES) == 0, "tile loads divide evenly");
+  static_assert(LOADS_PER_STEP == 8, "kWaitVm16 assumes 8 loads per wave per K-step");
 
   using Acc = f32x16_t[TM][TN];
 
   __device__ static inline int lane() { return threadIdx.x & 63; }
-  __device__ static inline int wave_m() { return (threadIdx.x >> 6) % WGM; }
-  __device__ static inline int wave_n() { return (threadIdx.x >> 6) / WGM; }
+  __device__ static inline int wave() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
+  __device__ static inline int wave_m() { return wave() % WGM; }
+  __device__ static inline int wave_n() { return wave() / WGM; }
   // Tile-relative coordinates of accumulator element v of block (i, j).
   __device__ static inline int m_of(int i, int v) {
     return wave_m() * WM + i * 32 + 8 * (v >> 2) + 4 * (lane() >> 5) + (v & 3);
   }
   __device__ static inline int n_of(int j) { return wave_n() * WN + j * 32 + (lane() & 31); }
 
-  // Row (within the tile) and chunk of this thread's p-th 16-byte piece of a tile load.
-  __device__ static inline int ld_row(int p) { return (threadIdx.x >> 3) + p * ROWS_PER_PASS; }
-  __device__ static inline int ld_chunk() { return threadIdx.x & 7; }
+  __device__ static inline int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 3; }
+
+  // Tile row that this lane fetches in the wave's q-th load of A (or B), and the byte offset
+  // inside that row's 64-byte K slice that it must fetch to realise the swizzled layout.
+  __device__ static inline int ldA_row(int q) { return (wave() * A_LD + q) * 16 + (lane() >> 2); }
+  __device__ static inline int ldB_row(int q) { return (wave() * B_LD + q) * 16 + (lane() >> 2); }
+  __device__ static inline int ld_byte(int row) { return ((lane() & 3) ^ swz(row)) << 4; }
 
   __device__ static inline void zero(Acc& acc) {
 #pragma unroll
@@ -98,80 +121,118 @@ struct GemmTile {
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   }
 
-  // acc += A_tile * B_tile^T over `ksteps` steps of 128 bytes.
-  // offA[p] / offB[p]: byte offset (from A / B) of this thread's p-th piece at k-step 0, i.e.
-  // row_index * pitch + ld_chunk() * 16, with the row index already clamped by the caller.
-  // `lds` must provide LDS_BYTES bytes, 16-byte aligned.  Ends with all waves past a barrier,
-  // so LDS may be reused by the caller right away.
-  __device__ static inline void run(Acc& acc, const char* __restrict__ A, const int64_t (&offA)[A_CH],
-                                    const char* __restrict__ B, const int64_t (&offB)[B_CH],
+  // acc += A_tile * B_tile^T over `ksteps` steps of 64 bytes.
+  // A / B: uniform pointers to the tile's first row at K offset 0.  offA[q] / offB[q]: this
+  // lane's byte offset from that pointer for its q-th load: (row, already clamped by the caller,
+  // relative to the tile's first row) * pitch + ld_byte(row).
+  // `lds` must provide LDS_BYTES bytes.  Returns with every wave past a barrier and no load
+  // in flight, so LDS may be reused by the caller right away.
+  __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
+                                    const char* __restrict__ B, const uint32_t (&offB)[B_LD],
                                     int ksteps, char* lds) {
-    u32x4_t ra[A_CH], rb[B_CH];
-    const int c = ld_chunk();
-    int wofsA[A_CH], wofsB[B_CH];
-#pragma unroll
-    for (int p = 0; p < A_CH; ++p) {
-      const int r = ld_row(p);
-      wofsA[p] = r * 128 + ((c ^ (r & 7)) << 4);
-    }
-#pragma unroll
-    for (int p = 0; p < B_CH; ++p) {
-      const int r = ld_row(p);
-      wofsB[p] = BM * 128 + r * 128 + ((c ^ (r & 7)) << 4);
-    }
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int w = wave();
     const int l = lane();
     const int half = l >> 5;
     const int rA0 = wave_m() * WM + (l & 31);
     const int rB0 = wave_n() * WN + (l & 31);
 
-    auto gload = [&](int ks) {
-      const int64_t kofs = (int64_t)ks * 128;
+    auto issue = [&](int ks) {
+      char* st = lds + (ks & (NSTAGE - 1)) * STAGE;
+      const char* pa = A + (int64_t)ks * KB;
+      const char* pb = B + (int64_t)ks * KB;
 #pragma unroll
-      for (int p = 0; p < A_CH; ++p) ra[p] = *reinterpret_cast<const u32x4_t*>(A + offA[p] + kofs);
+      for (int q = 0; q < A_LD; ++q)
+        __builtin_amdgcn_global_load_lds((gptr_t)(pa + offA[q]), (lptr_t)(st + (w * A_LD + q) * 1024), 16, 0, 0);
 #pragma unroll
-      for (int p = 0; p < B_CH; ++p) rb[p] = *reinterpret_cast<const u32x4_t*>(B + offB[p] + kofs);
-    };
-    auto lstore = [&](char* stage) {
-#pragma unroll
-      for (int p = 0; p < A_CH; ++p) *reinterpret_cast<u32x4_t*>(stage + wofsA[p]) = ra[p];
-#pragma unroll
-      for (int p = 0; p < B_CH; ++p) *reinterpret_cast<u32x4_t*>(stage + wofsB[p]) = rb[p];
-    };
-    auto compute = [&](const char* stage) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        u32x4_t fa[TM], fb[TN];
-        const int ch = 2 * s + half;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int r = rA0 + i * 32;
-          fa[i] = *reinterpret_cast<const u32x4_t*>(stage + r * 128 + ((ch ^ (r & 7)) << 4));
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int r = rB0 + j * 32;
-          fb[j] = *reinterpret_cast<const u32x4_t*>(stage + BM * 128 + r * 128 + ((ch ^ (r & 7)) << 4));
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j) Elem<E>::mma(acc[i][j], fa[i], fb[j]);
-      }
+      for (int q = 0; q < B_LD; ++q)
+        __builtin_amdgcn_global_load_lds((gptr_t)(pb + offB[q]),
+                                         (lptr_t)(st + BM * KB + (w * B_LD + q) * 1024), 16, 0, 0);
     };
 
+    u32x4_t fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const char* stage, int s, int buf) {
+      const int ch = 2 * s + half;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = rA0 + i * 32;
+        fa[buf][i] = *reinterpret_cast<const u32x4_t*>(stage + r * KB + ((ch ^ swz(r)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r = rB0 + j * 32;
+        fb[buf][j] = *reinterpret_cast<const u32x4_t*>(stage + BM * KB + r * KB + ((ch ^ swz(r)) << 4));
+      }
+    };
+    auto mma_all = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) Elem<E>::mma(acc[i][j], fa[buf][i], fb[buf][j]);
+    };
+
+    // Scheduling hints: interleave one LDS read (then one global->LDS load) with each MFMA so
+    // that neither the fragment reads nor the load issue ever leave the matrix pipe idle.
+    constexpr int kDsRead = 0x100, kVmem = 0x010;
+    constexpr int MMAS = TM * TN * (Elem<E>::size == 2 ? 1 : 4);
+    constexpr int FR = TM + TN;
+
     if (ksteps <= 0) return;
-    gload(0);
-    lstore(lds);
-    __syncthreads();
-    for (int ks = 0; ks < ksteps; ++ks) {
-      char* cur = lds + (ks & 1) * STAGE;
-      char* nxt = lds + ((ks & 1) ^ 1) * STAGE;
-      const bool more = ks + 1 < ksteps;
-      if (more) gload(ks + 1);
-      compute(cur);
-      if (more) lstore(nxt);
-      __syncthreads();
+    const int pre = ksteps < NSTAGE - 1 ? ksteps : NSTAGE - 1;
+    for (int ks = 0; ks < pre; ++ks) issue(ks);
+    if (ksteps >= NSTAGE - 1)
+      __builtin_amdgcn_s_waitcnt(kWaitVm16);
+    else
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_barrier();
+    read_frags(lds, 0, 0);
+    int ks = 0;
+    // steady state: three K-steps of loads in flight, straight-line body
+    for (; ks + NSTAGE - 1 < ksteps; ++ks) {
+      read_frags(lds + (ks & (NSTAGE - 1)) * STAGE, 1, 1);
+      issue(ks + NSTAGE - 1);   // refills the stage whose reads ended before the last barrier
+      mma_all(0);
+#pragma unroll
+      for (int i = 0; i < FR; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < LOADS_PER_STEP; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, MMAS - FR - LOADS_PER_STEP, 0);
+      __builtin_amdgcn_sched_barrier(0);        // nothing is scheduled across the stage hand-over
+      __builtin_amdgcn_s_waitcnt(kWaitVm16);    // this wave's loads of K-step ks+1 have landed
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // and its reads of the current stage are complete
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(lds + ((ks + 1) & (NSTAGE - 1)) * STAGE, 0, 0);
+      mma_all(1);
+#pragma unroll
+      for (int i = 0; i < FR; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, MMAS - FR, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // drain: nothing left to issue
+    for (; ks < ksteps; ++ks) {
+      read_frags(lds + (ks & (NSTAGE - 1)) * STAGE, 1, 1);
+      mma_all(0);
+      if (ks + 1 < ksteps) {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        __builtin_amdgcn_s_barrier();
+        read_frags(lds + ((ks + 1) & (NSTAGE - 1)) * STAGE, 0, 0);
+      }
+      mma_all(1);
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    __builtin_amdgcn_s_barrier();
   }
 };
 

@@ -48,15 +48,18 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   const int total_tiles = (a.V + G::BM - 1) / G::BM;
   const int t_lo = chunk * a.tiles_per_chunk;
   const int t_hi = min(t_lo + a.tiles_per_chunk, total_tiles);
-  const int ksteps = a.d * Elem<E>::size / kKBytes;
+  const int ksteps = a.d * Elem<E>::size / G::KB;
   const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
-  const char* Hc = static_cast<const char*>(a.Hc);
+  const char* Hc = static_cast<const char*>(a.Hc) + n0 * pitchH;
   const char* W = static_cast<const char*>(a.W);
 
-  int64_t offB[G::B_CH];
+  uint32_t offB[G::B_LD];
 #pragma unroll
-  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchH + G::ld_chunk() * 16;
+  for (int q = 0; q < G::B_LD; ++q) {
+    const int row = G::ldB_row(q);
+    offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
+  }
 
   int tokj[G::TN];
   float mr[G::TN], sr[G::TN], tr[G::TN];
@@ -70,13 +73,15 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 
   for (int tile = t_lo; tile < t_hi; ++tile) {
     const int m0 = tile * G::BM;
-    int64_t offA[G::A_CH];
+    uint32_t offA[G::A_LD];
 #pragma unroll
-    for (int p = 0; p < G::A_CH; ++p)
-      offA[p] = (int64_t)min(m0 + G::ld_row(p), a.V - 1) * pitchW + G::ld_chunk() * 16;
+    for (int q = 0; q < G::A_LD; ++q) {
+      const int row = G::ldA_row(q);
+      offA[q] = (uint32_t)((min(m0 + row, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
+    }
     typename G::Acc acc;
     G::zero(acc);
-    G::run(acc, W, offA, Hc, offB, ksteps, smem);
+    G::run(acc, W + (int64_t)m0 * pitchW, offA, Hc, offB, ksteps, smem);
 
     // target-logit capture: only where some lane's target falls inside this tile
     bool hit = false;
@@ -205,20 +210,26 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   const int64_t n0 = (int64_t)blockIdx.x * G::BN;
   const int mrel0 = blockIdx.y * G::BM;  // within the chunk
   const int m0 = a.c0 + mrel0;
-  const int ksteps = a.d * Elem<E>::size / kKBytes;
+  const int ksteps = a.d * Elem<E>::size / G::KB;
   const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
 
-  int64_t offA[G::A_CH], offB[G::B_CH];
+  uint32_t offA[G::A_LD], offB[G::B_LD];
 #pragma unroll
-  for (int p = 0; p < G::A_CH; ++p)
-    offA[p] = (int64_t)min(m0 + G::ld_row(p), a.V - 1) * pitchW + G::ld_chunk() * 16;
+  for (int q = 0; q < G::A_LD; ++q) {
+    const int row = G::ldA_row(q);
+    offA[q] = (uint32_t)((min(m0 + row, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
+  }
 #pragma unroll
-  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchH + G::ld_chunk() * 16;
+  for (int q = 0; q < G::B_LD; ++q) {
+    const int row = G::ldB_row(q);
+    offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
+  }
 
   typename G::Acc acc;
   G::zero(acc);
-  G::run(acc, static_cast<const char*>(a.W), offA, static_cast<const char*>(a.Hc), offB, ksteps, smem);
+  G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
+         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
 
   char* dZ = static_cast<char*>(a.dZ);
   char* dZT = static_cast<char*>(a.dZT);
@@ -261,19 +272,26 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   if (n0 >= n_lim) return;
   const int m0 = blockIdx.x * G::BM;
   const int64_t kel = a.k_from_nv ? (int64_t)nv : a.K;
-  const int ksteps = (int)((kel * Elem<E>::size + kKBytes - 1) / kKBytes);
+  const int ksteps = (int)((kel * Elem<E>::size + G::KB - 1) / G::KB);
   const int64_t pitchA = a.ldA * Elem<E>::size;
   const int64_t pitchB = a.ldB * Elem<E>::size;
 
-  int64_t offA[G::A_CH], offB[G::B_CH];
+  uint32_t offA[G::A_LD], offB[G::B_LD];
 #pragma unroll
-  for (int p = 0; p < G::A_CH; ++p) offA[p] = (int64_t)(m0 + G::ld_row(p)) * pitchA + G::ld_chunk() * 16;
+  for (int q = 0; q < G::A_LD; ++q) {
+    const int row = G::ldA_row(q);
+    offA[q] = (uint32_t)(row * pitchA) + G::ld_byte(row);
+  }
 #pragma unroll
-  for (int p = 0; p < G::B_CH; ++p) offB[p] = (n0 + G::ld_row(p)) * pitchB + G::ld_chunk() * 16;
+  for (int q = 0; q < G::B_LD; ++q) {
+    const int row = G::ldB_row(q);
+    offB[q] = (uint32_t)(row * pitchB) + G::ld_byte(row);
+  }
 
   typename G::Acc acc;
   G::zero(acc);
-  G::run(acc, static_cast<const char*>(a.A), offA, static_cast<const char*>(a.B), offB, ksteps, smem);
+  G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA,
+         static_cast<const char*>(a.B) + n0 * pitchB, offB, ksteps, smem);
 
 #pragma unroll
   for (int j = 0; j < G::TN; ++j) {
