@@ -37,6 +37,10 @@ struct WsLayout {
   int64_t dp;       // d rounded up to the tile
   int64_t Vc;       // vocabulary chunk (multiple of the tile)
   int64_t nchunks;  // number of vocabulary chunks
+  // Row pitches (elements) of the workspace matrices.  Each is its logical width plus one
+  // 128-byte line: a power-of-two pitch would put every row of a tile on the same L2
+  // channel and set (the token-major operands have a pitch of Ncap elements, often 2^k).
+  int64_t ldHc, ldHcT, ldWT, ldZ, ldZT;
   size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, total;
 };
 
@@ -72,11 +76,17 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   L.lse_c = take((size_t)L.Ncap * 4);
   L.zy = take((size_t)L.Ncap * 4);
   L.part = take((size_t)3 * L.nchunks * L.Ncap * 4);
-  L.Hc = take((size_t)L.Ncap * d->d * L.esz);
-  L.HcT = take((size_t)L.dp * L.Ncap * L.esz);
-  L.WT = take((size_t)L.dp * L.Vp * L.esz);
-  L.dZ = take((size_t)L.Ncap * L.Vc * L.esz);
-  L.dZT = take((size_t)L.Vc * L.Ncap * L.esz);
+  const int64_t pad = 128 / L.esz;
+  L.ldHc = d->d + pad;
+  L.ldHcT = L.Ncap + pad;
+  L.ldWT = L.Vp + pad;
+  L.ldZ = L.Vc + pad;
+  L.ldZT = L.Ncap + pad;
+  L.Hc = take((size_t)L.Ncap * L.ldHc * L.esz);
+  L.HcT = take((size_t)L.dp * L.ldHcT * L.esz);
+  L.WT = take((size_t)L.dp * L.ldWT * L.esz);
+  L.dZ = take((size_t)L.Ncap * L.ldZ * L.esz);
+  L.dZT = take((size_t)L.Vc * L.ldZT * L.esz);
   L.total = off;
   return L;
 }
@@ -91,17 +101,18 @@ hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t
 // (range-checked), and optionally g_logp and lse.  zy is cleared.
 hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
                           const float* g, const float* lse, int64_t N, WsHeader* hdr,
-                          const int32_t* row_slot, void* Hc, int32_t* tok_c, float* g_c,
+                          const int32_t* row_slot, void* Hc, int64_t ldHc, int32_t* tok_c, float* g_c,
                           float* lse_c, float* zy, hipStream_t s);
 
 // out[c][r] = in[r][c] for r < rows (rows read from the header when rows_from_nv), zero padding
-// up to out's full extent [cols_p x ld_out].
+// up to out's extent [cols_p x rows_p] (pitch ld_out >= rows_p).
 hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows_cap, int cols,
                             bool rows_from_nv, const WsHeader* hdr, void* out, int64_t ld_out,
-                            int64_t cols_p, hipStream_t s);
+                            int64_t rows_p, int64_t cols_p, hipStream_t s);
 
 struct FwdArgs {
-  const void* Hc;      // [Ncap x d] dense
+  const void* Hc;      // [Ncap x d], pitch ldHc
+  int64_t ldHc;
   const void* W;       // [V x d], stride ldW
   int64_t ldW;
   int d, V;
@@ -122,19 +133,21 @@ hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int6
 
 struct DzArgs {
   const void* Hc;
+  int64_t ldHc;
   const void* W;
   int64_t ldW;
   int d, V;
   int64_t Ncap;
-  int64_t Vc;     // chunk width (columns of dZ)
+  int64_t ldZ;    // pitch of dZ (elements)
+  int64_t ldZT;   // pitch of dZT (elements)
   int c0;         // first vocabulary id of the chunk
   int ntiles;     // vocabulary tiles in this chunk
   const int32_t* tok_c;
   const float* g_c;
   const float* lse_c;
   const WsHeader* hdr;
-  void* dZ;       // [Ncap x Vc]
-  void* dZT;      // [Vc x Ncap]
+  void* dZ;       // [Ncap x chunk], pitch ldZ
+  void* dZT;      // [chunk x Ncap], pitch ldZT
 };
 hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s);
 

@@ -5,26 +5,26 @@
 // A workgroup owns a BM x BN tile of C; each wavefront owns a (BM/WGM) x (BN/WGN)
 // sub-tile built from 32x32 MFMA blocks.
 //
-// Data movement: K is consumed 64 bytes per row per step (32 bf16 or 16 fp32).  Tiles go
+// Data movement: K is consumed 128 bytes per row per step (64 bf16 or 32 fp32), i.e. one
+// full cache line per row: the vector L1 moves one 128-byte line per ~2 clocks whether or
+// not all of it is used, so half-line steps would halve the load throughput.  Tiles go
 // from global memory straight into LDS (global_load_lds_dwordx4, no register staging)
-// through a ring of four stages, so three K-steps of loads are always in flight behind
-// the one being multiplied.  One workgroup barrier per K-step; completion of a stage is
-// tracked with the wave's own vmcnt (loads retire in order) followed by that barrier.
+// into two alternating stages; the loads of K-step k+2 are issued right after the barrier
+// that retires K-step k.  One workgroup barrier per K-step; a stage is complete when each
+// wave's own vmcnt has drained and all waves have passed that barrier.
 //
-// LDS stage layout: A rows then B rows, 64 bytes (four 16-byte chunks) per row; chunk c
+// LDS stage layout: A rows then B rows, 128 bytes (eight 16-byte chunks) per row; chunk c
 // of row r sits at chunk position c ^ swz(r).  A direct-to-LDS load writes lane L's 16
-// bytes at wave_base + 16 L, i.e. row L/4, position L%4 of a 16-row group, so lane L
-// simply fetches the global chunk (L%4) ^ swz(row).  swz is chosen so that the 128-bit
-// fragment reads (32 consecutive rows, fixed chunk) are bank-conflict-free whether the
-// hardware serves 8 lanes over 32 banks or 16 lanes over 64 banks per cycle.
+// bytes at wave_base + 16 L, i.e. row L/8, position L%8 of an 8-row group, so lane L
+// simply fetches the global chunk (L%8) ^ swz(row).
 //
 // Fragment layout used for both operands (what matters is only that A and B agree):
 // lane l of a 32-row block holds row l % 32 and the 16-byte chunk 2*s + l/32 of K
-// sub-step s (two sub-steps per K-step).  For bf16 one v_mfma_f32_32x32x16_bf16 consumes
+// sub-step s (four sub-steps per K-step).  For bf16 one v_mfma_f32_32x32x16_bf16 consumes
 // the chunk; for fp32 the chunk's four floats feed four v_mfma_f32_32x32x2_f32.
 // Fragments are double-buffered in registers and the pipeline is skewed so that the
-// barrier falls between the two sub-steps: the MFMAs of sub-step 1 overlap the first
-// fragment reads of the next stage.
+// barrier falls before the last sub-step: its MFMAs overlap the first fragment reads of
+// the next stage and the issue of the next loads.
 //
 // Accumulator layout of a 32x32 block (16 floats per lane):
 //   element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4,  n = l % 32.
@@ -70,9 +70,54 @@ struct Elem<f32_tag> {
 };
 
 // s_waitcnt immediates (gfx9 encoding): only the named counter is constrained.
-constexpr int kWaitVm0 = 0x0F70;
-constexpr int kWaitVm16 = 0x4F70;
+constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int kWaitVm0 = wait_vm(0);
 constexpr int kWaitLgkm0 = 0xC07F;
+
+// Workgroup -> tile mapping that keeps L2 traffic local to an XCD.
+//
+// The chip dispatches workgroup i of a 1-D grid to XCD i % 8, and each XCD has a private L2.
+// A work grid of X x Y items (x selects the A-side operand slab, y the B-side slab) is cut
+// into eight contiguous y-ranges, one per XCD; inside its range an XCD walks blocks of
+// bx x by items (x fastest), so the 32 workgroups it runs at a time cover a compact block and
+// share bx + by operand slabs instead of fetching 64.  Returns false for workgroups beyond the
+// work (the grid is sized for the largest possible Y).
+constexpr int kNumXcd = 8;
+__device__ inline bool xcd_tile_coords(int wg, int X, int Y, int bx, int by, int& x, int& y) {
+  const int xcd = wg % kNumXcd;
+  const int j = wg / kNumXcd;
+  const int y_per = (Y + kNumXcd - 1) / kNumXcd;
+  const int y_base = xcd * y_per;
+  const int y_cnt = min(y_per, Y - y_base);
+  if (y_cnt <= 0) return false;
+  const int per_yblk = X * by;
+  const int yb = j / per_yblk;
+  int r = j - yb * per_yblk;
+  const int h = min(by, y_cnt - yb * by);
+  if (h <= 0 || r >= X * h) return false;
+  const int nfull = X / bx;
+  const int full_items = nfull * bx * h;
+  int yin;
+  if (r < full_items) {
+    const int xb = r / (bx * h);
+    const int r2 = r - xb * (bx * h);
+    yin = r2 / bx;
+    x = xb * bx + (r2 - yin * bx);
+  } else {
+    const int tw = X - nfull * bx;
+    r -= full_items;
+    yin = r / tw;
+    x = nfull * bx + (r - yin * tw);
+  }
+  y = y_base + yb * by + yin;
+  return true;
+}
+// Grid size that covers every item for any Y <= Y_cap under the mapping above.
+inline unsigned xcd_grid_size(int X, long long Y_cap, int by) {
+  const long long y_per = (Y_cap + kNumXcd - 1) / kNumXcd;
+  const long long yblks = (y_per + by - 1) / by;
+  return (unsigned)(kNumXcd * yblks * by * X);
+}
 
 template <typename E, int BM_, int BN_, int WGM_, int WGN_>
 struct GemmTile {
@@ -81,16 +126,17 @@ struct GemmTile {
   static constexpr int NT = 64 * NWAVES;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 32, TN = WN / 32;
-  static constexpr int KB = 64;                       // bytes of K per row per step
-  static constexpr int NSTAGE = 4;
+  static constexpr int KB = 128;                      // bytes of K per row per step (a cache line)
+  static constexpr int NSUB = KB / 32;                // K sub-steps (one fragment pair each)
+  static constexpr int NSTAGE = 2;
   static constexpr int STAGE = (BM + BN) * KB;
   static constexpr int LDS_BYTES = NSTAGE * STAGE;
-  static constexpr int A_LD = BM / 16 / NWAVES;       // direct-to-LDS load instructions per wave
-  static constexpr int B_LD = BN / 16 / NWAVES;       // per K-step (each moves 16 rows)
+  static constexpr int A_LD = BM / 8 / NWAVES;        // direct-to-LDS load instructions per wave
+  static constexpr int B_LD = BN / 8 / NWAVES;        // per K-step (each moves 8 rows)
   static constexpr int LOADS_PER_STEP = A_LD + B_LD;
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tiles are 32x32 blocks");
-  static_assert(BM % (16 * NWAVES) == 0 && BN % (16 * NWAVES) == 0, "tile loads divide evenly");
-  static_assert(LOADS_PER_STEP == 8, "kWaitVm16 assumes 8 loads per wave per K-step");
+  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile loads divide evenly");
+  static_assert(NSUB % 2 == 0, "fragment double-buffering assumes an even number of sub-steps");
 
   using Acc = f32x16_t[TM][TN];
 
@@ -104,13 +150,13 @@ struct GemmTile {
   }
   __device__ static inline int n_of(int j) { return wave_n() * WN + j * 32 + (lane() & 31); }
 
-  __device__ static inline int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 3; }
+  __device__ static inline int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
   // Tile row that this lane fetches in the wave's q-th load of A (or B), and the byte offset
-  // inside that row's 64-byte K slice that it must fetch to realise the swizzled layout.
-  __device__ static inline int ldA_row(int q) { return (wave() * A_LD + q) * 16 + (lane() >> 2); }
-  __device__ static inline int ldB_row(int q) { return (wave() * B_LD + q) * 16 + (lane() >> 2); }
-  __device__ static inline int ld_byte(int row) { return ((lane() & 3) ^ swz(row)) << 4; }
+  // inside that row's 128-byte K slice that it must fetch to realise the swizzled layout.
+  __device__ static inline int ldA_row(int q) { return (wave() * A_LD + q) * 8 + (lane() >> 3); }
+  __device__ static inline int ldB_row(int q) { return (wave() * B_LD + q) * 8 + (lane() >> 3); }
+  __device__ static inline int ld_byte(int row) { return ((lane() & 7) ^ swz(row)) << 4; }
 
   __device__ static inline void zero(Acc& acc) {
 #pragma unroll
@@ -121,7 +167,7 @@ struct GemmTile {
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   }
 
-  // acc += A_tile * B_tile^T over `ksteps` steps of 64 bytes.
+  // acc += A_tile * B_tile^T over `ksteps` steps of 128 bytes.
   // A / B: uniform pointers to the tile's first row at K offset 0.  offA[q] / offB[q]: this
   // lane's byte offset from that pointer for its q-th load: (row, already clamped by the caller,
   // relative to the tile's first row) * pitch + ld_byte(row).
@@ -153,6 +199,10 @@ struct GemmTile {
 
     u32x4_t fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* stage, int s, int buf) {
+#ifdef LMHEAD_UB_NO_FRAG
+      (void)stage; (void)s; (void)buf;
+      return;
+#endif
       const int ch = 2 * s + half;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -166,70 +216,79 @@ struct GemmTile {
       }
     };
     auto mma_all = [&](int buf) {
+#ifdef LMHEAD_UB_NO_MMA
+      (void)buf;
+      return;
+#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) Elem<E>::mma(acc[i][j], fa[buf][i], fb[buf][j]);
     };
 
-    // Scheduling hints: interleave one LDS read (then one global->LDS load) with each MFMA so
-    // that neither the fragment reads nor the load issue ever leave the matrix pipe idle.
-    constexpr int kDsRead = 0x100, kVmem = 0x010;
+    // Scheduling hints: one LDS read (then global->LDS loads) behind each MFMA so that neither
+    // the fragment reads nor the load issue leave the matrix pipe idle.
+    constexpr int kDsRead = 0x100, kVmem = 0x010, kMfma = 0x008;
     constexpr int MMAS = TM * TN * (Elem<E>::size == 2 ? 1 : 4);
     constexpr int FR = TM + TN;
-
-    if (ksteps <= 0) return;
-    const int pre = ksteps < NSTAGE - 1 ? ksteps : NSTAGE - 1;
-    for (int ks = 0; ks < pre; ++ks) issue(ks);
-    if (ksteps >= NSTAGE - 1)
-      __builtin_amdgcn_s_waitcnt(kWaitVm16);
-    else
-      __builtin_amdgcn_s_waitcnt(kWaitVm0);
-    __builtin_amdgcn_s_barrier();
-    read_frags(lds, 0, 0);
-    int ks = 0;
-    // steady state: three K-steps of loads in flight, straight-line body
-    for (; ks + NSTAGE - 1 < ksteps; ++ks) {
-      read_frags(lds + (ks & (NSTAGE - 1)) * STAGE, 1, 1);
-      issue(ks + NSTAGE - 1);   // refills the stage whose reads ended before the last barrier
-      mma_all(0);
+    static_assert(MMAS > FR, "more MFMAs than fragment reads per sub-step");
+    constexpr int LD_PER_SLOT = (LOADS_PER_STEP + (MMAS - FR) - 1) / (MMAS - FR);
+    constexpr int LD_SLOTS = (LOADS_PER_STEP + LD_PER_SLOT - 1) / LD_PER_SLOT;
+    auto sched_reads = [&]() {
 #pragma unroll
       for (int i = 0; i < FR; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
         __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
       }
+    };
+
+    if (ksteps <= 0) return;
+    issue(0);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_barrier();
+    if (ksteps > 1) issue(1);
+    read_frags(lds, 0, 0);
+    auto first_substeps = [&](const char* cur) {
 #pragma unroll
-      for (int i = 0; i < LOADS_PER_STEP; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
+      for (int sb = 0; sb < NSUB - 1; ++sb) {
+        read_frags(cur, sb + 1, (sb + 1) & 1);
+        mma_all(sb & 1);
+        sched_reads();
+        __builtin_amdgcn_sched_group_barrier(kMfma, MMAS - FR, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, MMAS - FR - LOADS_PER_STEP, 0);
-      __builtin_amdgcn_sched_barrier(0);        // nothing is scheduled across the stage hand-over
-      __builtin_amdgcn_s_waitcnt(kWaitVm16);    // this wave's loads of K-step ks+1 have landed
+    };
+    int ks = 0;
+    // steady state: hand the stage over, refill it, and start on the next one
+    for (; ks + 2 < ksteps; ++ks) {
+      first_substeps(lds + (ks & 1) * STAGE);
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);     // this wave's loads of K-step ks+1 have landed
       __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // and its reads of the current stage are complete
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(lds + ((ks + 1) & (NSTAGE - 1)) * STAGE, 0, 0);
+      read_frags(lds + ((ks & 1) ^ 1) * STAGE, 0, 0);
+      issue(ks + 2);                            // into the stage every wave has just left
       mma_all(1);
+      sched_reads();
 #pragma unroll
-      for (int i = 0; i < FR; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+      for (int i = 0; i < MMAS - FR; ++i) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        if (i < LD_SLOTS) __builtin_amdgcn_sched_group_barrier(kVmem, LD_PER_SLOT, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, MMAS - FR, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // drain: nothing left to issue
+    // drain: the last two K-steps have nothing left to issue
     for (; ks < ksteps; ++ks) {
-      read_frags(lds + (ks & (NSTAGE - 1)) * STAGE, 1, 1);
-      mma_all(0);
+      first_substeps(lds + (ks & 1) * STAGE);
       if (ks + 1 < ksteps) {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
-        read_frags(lds + ((ks + 1) & (NSTAGE - 1)) * STAGE, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(lds + ((ks & 1) ^ 1) * STAGE, 0, 0);
       }
       mma_all(1);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     __builtin_amdgcn_s_barrier();

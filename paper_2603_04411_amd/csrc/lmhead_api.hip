@@ -108,10 +108,11 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
   LM_TRY(launch_index(len, (int)L.R, desc->T, hdr, w.at<int32_t>(L.cu_len), w.at<int32_t>(L.row_slot),
                       mask, cu_len, s));
   LM_TRY(launch_compact(desc->dtype, H, desc->ldH, desc->d, desc->V, tok, nullptr, nullptr, L.N, hdr,
-                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), w.at<int32_t>(L.tok_c), nullptr,
+                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c), nullptr,
                         nullptr, w.at<float>(L.zy), s));
   FwdArgs fa{};
   fa.Hc = w.at<void>(L.Hc);
+  fa.ldHc = L.ldHc;
   fa.W = W;
   fa.ldW = desc->ldW;
   fa.d = desc->d;
@@ -151,12 +152,13 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
   LM_TRY(launch_index(len, (int)L.R, desc->T, hdr, w.at<int32_t>(L.cu_len), w.at<int32_t>(L.row_slot),
                       nullptr, nullptr, s));
   LM_TRY(launch_compact(dt, H, desc->ldH, desc->d, desc->V, tok, g_logp, lse, L.N, hdr,
-                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), w.at<int32_t>(L.tok_c),
+                        w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c),
                         w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), s));
   // K-contiguous copies of the two operands that the backward contracts along their rows
-  LM_TRY(launch_transpose(dt, w.at<void>(L.Hc), desc->d, L.Ncap, desc->d, true, hdr, w.at<void>(L.HcT),
-                          L.Ncap, L.dp, s));
-  LM_TRY(launch_transpose(dt, W, desc->ldW, desc->V, desc->d, false, hdr, w.at<void>(L.WT), L.Vp, L.dp, s));
+  LM_TRY(launch_transpose(dt, w.at<void>(L.Hc), L.ldHc, L.Ncap, desc->d, true, hdr, w.at<void>(L.HcT),
+                          L.ldHcT, L.Ncap, L.dp, s));
+  LM_TRY(launch_transpose(dt, W, desc->ldW, desc->V, desc->d, false, hdr, w.at<void>(L.WT), L.ldWT, L.Vp,
+                          L.dp, s));
   LM_TRY(launch_zero_padded_rows(dH, desc->d, len, (int)L.R, desc->T, s));
 
   const int total_tiles = (int)(L.Vp / kTile);
@@ -167,12 +169,14 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     const int c0 = t_lo * kTile;
     DzArgs za{};
     za.Hc = w.at<void>(L.Hc);
+    za.ldHc = L.ldHc;
     za.W = W;
     za.ldW = desc->ldW;
     za.d = desc->d;
     za.V = desc->V;
     za.Ncap = L.Ncap;
-    za.Vc = L.Vc;
+    za.ldZ = L.ldZ;
+    za.ldZT = L.ldZT;
     za.c0 = c0;
     za.ntiles = ntiles;
     za.tok_c = w.at<int32_t>(L.tok_c);
@@ -189,9 +193,9 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     // dH[slot(n)][m] (+)= sum_v W^T[m][c0 + v] dZ[n][v]
     GemmTArgs ha{};
     ha.A = w.at<char>(L.WT) + (size_t)c0 * L.esz;
-    ha.ldA = L.Vp;
+    ha.ldA = L.ldWT;
     ha.B = w.at<void>(L.dZ);
-    ha.ldB = L.Vc;
+    ha.ldB = L.ldZ;
     ha.M = desc->d;
     ha.n_from_nv = true;
     ha.k_from_nv = false;
@@ -210,9 +214,9 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     // dW[c0 + n][m] = sum_i Hc^T[m][i] dZ^T[n][i]
     GemmTArgs wa{};
     wa.A = w.at<void>(L.HcT);
-    wa.ldA = L.Ncap;
+    wa.ldA = L.ldHcT;
     wa.B = w.at<void>(L.dZT);
-    wa.ldB = L.Ncap;
+    wa.ldB = L.ldZT;
     wa.M = desc->d;
     wa.n_limit = (desc->V - c0 < ntiles * kTile) ? desc->V - c0 : ntiles * kTile;
     wa.n_from_nv = false;

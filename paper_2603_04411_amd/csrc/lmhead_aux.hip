@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void fill_index_kernel(const int32_t* __restri
 // One wavefront per compact row k: copies H[row_slot[k], :] (16 bytes per lane per step) or
 // zero-fills the rows between N_v and the next tile multiple.
 __global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H, int64_t pitchH,
-                                                      int row_bytes, int V,
+                                                      int row_bytes, int64_t pitchHc, int V,
                                                       const int32_t* __restrict__ tok,
                                                       const float* __restrict__ g,
                                                       const float* __restrict__ lse, WsHeader* hdr,
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H
   if (k >= nvp) return;
   const int lane = threadIdx.x & 63;
   typedef __attribute__((ext_vector_type(4))) uint32_t u4;
-  u4* dst = reinterpret_cast<u4*>(Hc + k * (int64_t)row_bytes);
+  u4* dst = reinterpret_cast<u4*>(Hc + k * pitchHc);
   const int nvec = row_bytes / 16;
   if (k < nv) {
     const int64_t slot = row_slot[k];
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
                                                         int64_t rows_fixed, int cols, int rows_from_nv,
                                                         const WsHeader* __restrict__ hdr,
                                                         T* __restrict__ out, int64_t ld_out,
-                                                        int64_t cols_p) {
+                                                        int64_t rows_p, int64_t cols_p) {
   __shared__ T tile[64][65];
   const int64_t rows = rows_from_nv ? (int64_t)hdr->nv : rows_fixed;
   const int64_t r0 = (int64_t)blockIdx.x * 64;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
   __syncthreads();
   for (int cc = ty; cc < 64; cc += 4) {
     const int64_t c = c0 + cc, r = r0 + tx;
-    if (c < cols_p && r < ld_out) out[c * ld_out + r] = tile[tx][cc];
+    if (c < cols_p && r < rows_p) out[c * ld_out + r] = tile[tx][cc];
   }
 }
 
@@ -235,28 +235,28 @@ hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t
 
 hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
                           const float* g, const float* lse, int64_t N, WsHeader* hdr,
-                          const int32_t* row_slot, void* Hc, int32_t* tok_c, float* g_c,
+                          const int32_t* row_slot, void* Hc, int64_t ldHc, int32_t* tok_c, float* g_c,
                           float* lse_c, float* zy, hipStream_t s) {
   const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
   const int64_t cap = (N + kTile - 1) / kTile * kTile;
   hipLaunchKernelGGL(compact_kernel, dim3((unsigned)(cap / 4)), dim3(256), 0, s,
-                     static_cast<const char*>(H), ldH * esz, d * esz, V, tok, g, lse, hdr, row_slot,
+                     static_cast<const char*>(H), ldH * esz, d * esz, ldHc * esz, V, tok, g, lse, hdr, row_slot,
                      static_cast<char*>(Hc), tok_c, g ? g_c : nullptr, lse ? lse_c : nullptr, zy);
   return hipGetLastError();
 }
 
 hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows_cap, int cols,
                             bool rows_from_nv, const WsHeader* hdr, void* out, int64_t ld_out,
-                            int64_t cols_p, hipStream_t s) {
-  const dim3 grid((unsigned)((ld_out + 63) / 64), (unsigned)((cols_p + 63) / 64));
+                            int64_t rows_p, int64_t cols_p, hipStream_t s) {
+  const dim3 grid((unsigned)((rows_p + 63) / 64), (unsigned)((cols_p + 63) / 64));
   if (dtype == LMHEAD_BF16) {
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
-                       hdr, static_cast<uint16_t*>(out), ld_out, cols_p);
+                       hdr, static_cast<uint16_t*>(out), ld_out, rows_p, cols_p);
   } else {
     hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s,
                        static_cast<const uint32_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
-                       hdr, static_cast<uint32_t*>(out), ld_out, cols_p);
+                       hdr, static_cast<uint32_t*>(out), ld_out, rows_p, cols_p);
   }
   return hipGetLastError();
 }

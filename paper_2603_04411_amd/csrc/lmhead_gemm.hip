@@ -22,8 +22,11 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+#ifndef LMHEAD_WAVES_N
+#define LMHEAD_WAVES_N 2
+#endif
 template <typename E>
-using Tile = GemmTile<E, 256, 256, 2, 2>;
+using Tile = GemmTile<E, 256, 256, 2, LMHEAD_WAVES_N>;
 
 // Merge (m2, s2, t2) into (m, s, t): statistics of a union of disjoint logit sets.
 __device__ inline void merge_stats(float& m, float& s, float& t, float m2, float s2, float t2) {
@@ -49,7 +52,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   const int t_lo = chunk * a.tiles_per_chunk;
   const int t_hi = min(t_lo + a.tiles_per_chunk, total_tiles);
   const int ksteps = a.d * Elem<E>::size / G::KB;
-  const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
+  const int64_t pitchH = a.ldHc * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
   const char* Hc = static_cast<const char*>(a.Hc) + n0 * pitchH;
   const char* W = static_cast<const char*>(a.W);
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   const int mrel0 = blockIdx.y * G::BM;  // within the chunk
   const int m0 = a.c0 + mrel0;
   const int ksteps = a.d * Elem<E>::size / G::KB;
-  const int64_t pitchH = (int64_t)a.d * Elem<E>::size;
+  const int64_t pitchH = a.ldHc * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
 
   uint32_t offA[G::A_LD], offB[G::B_LD];
@@ -252,10 +255,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
           dz[e] = (m0 + mt + e < a.V) ? g * (oh - p) : 0.f;
         }
         const int64_t mc = mrel0 + mt;
-        Store4<E>::row(dZ + ((size_t)n * a.Vc + mc) * Elem<E>::size, dz[0], dz[1], dz[2], dz[3]);
+        Store4<E>::row(dZ + ((size_t)n * a.ldZ + mc) * Elem<E>::size, dz[0], dz[1], dz[2], dz[3]);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          Store4<E>::one(dZT + ((size_t)(mc + e) * a.Ncap + n) * Elem<E>::size, dz[e]);
+          Store4<E>::one(dZT + ((size_t)(mc + e) * a.ldZT + n) * Elem<E>::size, dz[e]);
       }
   }
 }
