@@ -8,12 +8,18 @@
 // Data movement: K is consumed 128 bytes per row per step (64 bf16 or 32 fp32), i.e. one
 // full cache line per row: the vector L1 moves one 128-byte line per ~2 clocks whether or
 // not all of it is used, so half-line steps would halve the load throughput.  Tiles go
-// from global memory straight into LDS (global_load_lds_dwordx4, no register staging)
-// into two alternating stages; the loads of K-step k+2 are issued right after the barrier
-// that retires K-step k.  One workgroup barrier per K-step; a stage is complete when each
-// wave's own vmcnt has drained and all waves have passed that barrier.
+// from global memory straight into LDS (buffer_load_dwordx4 ... lds, no register staging).
+// LDS is a ring of five 32 KB slots, each holding one operand's tile for one K-step; the
+// units A(0) B(0) A(1) B(1) ... go round the ring, so besides the two units being
+// multiplied, three are resident or in flight.  During K-step k a wave issues the loads of
+// B(k+1) (first half of the step) and A(k+2) (second half) into the two slots that the
+// barrier ending K-step k-1 has freed, one load behind every fourth MFMA: the vector L1
+// then never sees a burst (a burst backs up the address queue and blocks the wave's
+// in-order issue, MFMAs included), and every load still has half a K-step or more to land.
+// One workgroup barrier per K-step; a unit is complete when each wave's own vmcnt has
+// drained past it (loads retire in order) and all waves have passed that barrier.
 //
-// LDS stage layout: A rows then B rows, 128 bytes (eight 16-byte chunks) per row; chunk c
+// LDS slot layout: 256 rows of 128 bytes (eight 16-byte chunks); chunk c
 // of row r sits at chunk position c ^ swz(r).  A direct-to-LDS load writes lane L's 16
 // bytes at wave_base + 16 L, i.e. row L/8, position L%8 of an 8-row group, so lane L
 // simply fetches the global chunk (L%8) ^ swz(row).
@@ -128,9 +134,9 @@ struct GemmTile {
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int KB = 128;                      // bytes of K per row per step (a cache line)
   static constexpr int NSUB = KB / 32;                // K sub-steps (one fragment pair each)
-  static constexpr int NSTAGE = 2;
-  static constexpr int STAGE = (BM + BN) * KB;
-  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int NSLOT = 5;                     // ring of operand-tile slots
+  static constexpr int SLOT = (BM > BN ? BM : BN) * KB;
+  static constexpr int LDS_BYTES = NSLOT * SLOT;
   static constexpr int A_LD = BM / 8 / NWAVES;        // direct-to-LDS load instructions per wave
   static constexpr int B_LD = BN / 8 / NWAVES;        // per K-step (each moves 8 rows)
   static constexpr int LOADS_PER_STEP = A_LD + B_LD;
@@ -176,7 +182,6 @@ struct GemmTile {
   __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                     const char* __restrict__ B, const uint32_t (&offB)[B_LD],
                                     int ksteps, char* lds) {
-    typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int w = wave();
     const int l = lane();
@@ -184,35 +189,43 @@ struct GemmTile {
     const int rA0 = wave_m() * WM + (l & 31);
     const int rB0 = wave_n() * WN + (l & 31);
 
-    auto issue = [&](int ks) {
-      char* st = lds + (ks & (NSTAGE - 1)) * STAGE;
-      const char* pa = A + (int64_t)ks * KB;
-      const char* pb = B + (int64_t)ks * KB;
+    // Loads of one operand tile for K-step ks into ring slot `slot`; `part` selects which of
+    // the NPART groups of this wave's load instructions to issue.
+    constexpr int NPART = 2;
+    static_assert(A_LD % NPART == 0 && B_LD % NPART == 0, "loads split evenly over the regions");
+    // Raw buffer descriptors over each operand tile: base = the tile's first row, 2 GiB window,
+    // so a load needs one 32-bit VGPR offset (row * pitch + byte) and a scalar K offset.
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, 0x7fffffff, 0x00020000);
+    auto issue_a = [&](int ks, int slot, int part) {
+      char* st = lds + slot * SLOT;
 #pragma unroll
-      for (int q = 0; q < A_LD; ++q)
-        __builtin_amdgcn_global_load_lds((gptr_t)(pa + offA[q]), (lptr_t)(st + (w * A_LD + q) * 1024), 16, 0, 0);
+      for (int q = part * (A_LD / NPART); q < (part + 1) * (A_LD / NPART); ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(st + (w * A_LD + q) * 1024), 16, offA[q], ks * KB, 0, 0);
+    };
+    auto issue_b = [&](int ks, int slot, int part) {
+      char* st = lds + slot * SLOT;
 #pragma unroll
-      for (int q = 0; q < B_LD; ++q)
-        __builtin_amdgcn_global_load_lds((gptr_t)(pb + offB[q]),
-                                         (lptr_t)(st + BM * KB + (w * B_LD + q) * 1024), 16, 0, 0);
+      for (int q = part * (B_LD / NPART); q < (part + 1) * (B_LD / NPART); ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(st + (w * B_LD + q) * 1024), 16, offB[q], ks * KB, 0, 0);
     };
 
     u32x4_t fa[2][TM], fb[2][TN];
-    auto read_frags = [&](const char* stage, int s, int buf) {
+    auto read_frags = [&](const char* sa, const char* sb, int s, int buf) {
 #ifdef LMHEAD_UB_NO_FRAG
-      (void)stage; (void)s; (void)buf;
+      (void)sa; (void)sb; (void)s; (void)buf;
       return;
 #endif
       const int ch = 2 * s + half;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int r = rA0 + i * 32;
-        fa[buf][i] = *reinterpret_cast<const u32x4_t*>(stage + r * KB + ((ch ^ swz(r)) << 4));
+        fa[buf][i] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + ((ch ^ swz(r)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int r = rB0 + j * 32;
-        fb[buf][j] = *reinterpret_cast<const u32x4_t*>(stage + BM * KB + r * KB + ((ch ^ swz(r)) << 4));
+        fb[buf][j] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + ((ch ^ swz(r)) << 4));
       }
     };
     auto mma_all = [&](int buf) {
@@ -226,69 +239,116 @@ struct GemmTile {
         for (int j = 0; j < TN; ++j) Elem<E>::mma(acc[i][j], fa[buf][i], fb[buf][j]);
     };
 
-    // Scheduling hints: one LDS read (then global->LDS loads) behind each MFMA so that neither
-    // the fragment reads nor the load issue leave the matrix pipe idle.
+    // Scheduling hints: behind each MFMA of a region one fragment read, and behind every
+    // (MMAS / loads)-th MFMA one global->LDS load, so that nothing leaves the matrix pipe idle.
     constexpr int kDsRead = 0x100, kVmem = 0x010, kMfma = 0x008;
     constexpr int MMAS = TM * TN * (Elem<E>::size == 2 ? 1 : 4);
     constexpr int FR = TM + TN;
-    static_assert(MMAS > FR, "more MFMAs than fragment reads per sub-step");
-    constexpr int LD_PER_SLOT = (LOADS_PER_STEP + (MMAS - FR) - 1) / (MMAS - FR);
-    constexpr int LD_SLOTS = (LOADS_PER_STEP + LD_PER_SLOT - 1) / LD_PER_SLOT;
-    auto sched_reads = [&]() {
+    constexpr int LD_REGION = A_LD / NPART;     // loads per region (A_LD == B_LD is not required
+    constexpr int LD_REGION_B = B_LD / NPART;   // but both are spread the same way)
+    static_assert(MMAS - (FR + 1) / 2 >= LD_REGION && MMAS - (FR + 1) / 2 >= LD_REGION_B, "region too short");
+    // (program order is reads, loads, MFMAs; the loads must stay behind the reads because both
+    // touch LDS, so the reads go two per MFMA up front and the loads are spread over the rest)
+    auto sched_region = [&](int nloads) {
+      constexpr int RD_SLOTS = (FR + 1) / 2;
 #pragma unroll
-      for (int i = 0; i < FR; ++i) {
+      for (int i = 0; i < MMAS; ++i) {
         __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+        if (i < RD_SLOTS) {
+          if (i == RD_SLOTS - 1 && (FR & 1))
+            __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+          else
+            __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
+        }
+        if (nloads > 0 && i >= RD_SLOTS) {
+          const int gap = (MMAS - RD_SLOTS) / nloads;
+          const int j = i - RD_SLOTS + 1;
+          if (j % gap == 0 && j / gap <= nloads) __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);
     };
+    auto next_slot = [](int s, int by) { s += by; return s >= NSLOT ? s - NSLOT : s; };
 
     if (ksteps <= 0) return;
-    issue(0);
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    // ring state: slots of A(ks) and B(ks); unit u lives in slot u % NSLOT
+    int sA = 0, sB = 1;
+    issue_a(0, 0, 0); issue_a(0, 0, 1);
+    issue_b(0, 1, 0); issue_b(0, 1, 1);
+    if (ksteps > 1) { issue_a(1, 2, 0); issue_a(1, 2, 1); }
+    if (ksteps > 1)
+      __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
+    else
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __builtin_amdgcn_s_barrier();
-    if (ksteps > 1) issue(1);
-    read_frags(lds, 0, 0);
-    auto first_substeps = [&](const char* cur) {
-#pragma unroll
-      for (int sb = 0; sb < NSUB - 1; ++sb) {
-        read_frags(cur, sb + 1, (sb + 1) & 1);
-        mma_all(sb & 1);
-        sched_reads();
-        __builtin_amdgcn_sched_group_barrier(kMfma, MMAS - FR, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    };
+    read_frags(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     int ks = 0;
-    // steady state: hand the stage over, refill it, and start on the next one
+    // Steady state.  Entering K-step ks: A(ks), B(ks), A(ks+1) are resident or in flight; the
+    // slots of A(ks-1) and B(ks-1) are free (all waves passed the barrier after reading them).
     for (; ks + 2 < ksteps; ++ks) {
-      first_substeps(lds + (ks & 1) * STAGE);
-      __builtin_amdgcn_s_waitcnt(kWaitVm0);     // this wave's loads of K-step ks+1 have landed
-      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // and its reads of the current stage are complete
+      const char* ca = lds + sA * SLOT;
+      const char* cb = lds + sB * SLOT;
+      const int sB1 = next_slot(sB, 2);   // slot of B(ks+1) == slot of A(ks-1)
+      const int sA1 = next_slot(sA, 2);   // slot of A(ks+1)
+      const int sA2 = next_slot(sA1, 2);  // slot of A(ks+2) == slot of B(ks-1)
+      // sub-step 0 and 1: first and second half of B(ks+1)
+      read_frags(ca, cb, 1, 1);
+      issue_b(ks + 1, sB1, 0);
+      mma_all(0);
+      sched_region(LD_REGION_B);
+      read_frags(ca, cb, 2, 0);
+      issue_b(ks + 1, sB1, 1);
+      mma_all(1);
+      sched_region(LD_REGION_B);
+      // sub-step 2: first half of A(ks+2)
+      read_frags(ca, cb, 3, 1);
+      issue_a(ks + 2, sA2, 0);
+      mma_all(0);
+      sched_region(LD_REGION);
+      // hand-over: everything but the youngest A_LD/2 loads of this wave has landed
+      __builtin_amdgcn_s_waitcnt(wait_vm(A_LD / NPART));
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(lds + ((ks & 1) ^ 1) * STAGE, 0, 0);
-      issue(ks + 2);                            // into the stage every wave has just left
+      // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of A(ks+2);
+      // its target slot was freed by the barrier that ended K-step ks-1, not by this one
+      read_frags(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+      issue_a(ks + 2, sA2, 1);
       mma_all(1);
-      sched_reads();
-#pragma unroll
-      for (int i = 0; i < MMAS - FR; ++i) {
-        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-        if (i < LD_SLOTS) __builtin_amdgcn_sched_group_barrier(kVmem, LD_PER_SLOT, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+      sched_region(LD_REGION);
+      sA = sA1;
+      sB = sB1;
     }
-    // drain: the last two K-steps have nothing left to issue
+    // drain: the last two K-steps
     for (; ks < ksteps; ++ks) {
-      first_substeps(lds + (ks & 1) * STAGE);
-      if (ks + 1 < ksteps) {
+      const char* ca = lds + sA * SLOT;
+      const char* cb = lds + sB * SLOT;
+      const int sB1 = next_slot(sB, 2);
+      const int sA1 = next_slot(sA, 2);
+      const bool more = ks + 1 < ksteps;
+      read_frags(ca, cb, 1, 1);
+      if (more) issue_b(ks + 1, sB1, 0);
+      mma_all(0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(ca, cb, 2, 0);
+      if (more) issue_b(ks + 1, sB1, 1);
+      mma_all(1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(ca, cb, 3, 1);
+      mma_all(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(lds + ((ks & 1) ^ 1) * STAGE, 0, 0);
+        read_frags(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
       }
       mma_all(1);
       __builtin_amdgcn_sched_barrier(0);
+      sA = sA1;
+      sB = sB1;
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     __builtin_amdgcn_s_barrier();
