@@ -195,8 +195,16 @@ struct GemmTile {
     static_assert(A_LD % NPART == 0 && B_LD % NPART == 0, "loads split evenly over the regions");
     // Raw buffer descriptors over each operand tile: base = the tile's first row, 2 GiB window,
     // so a load needs one 32-bit VGPR offset (row * pitch + byte) and a scalar K offset.
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, 0x7fffffff, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, 0x7fffffff, 0x00020000);
+    // The tile pointers are wave-uniform by construction; saying so explicitly keeps the
+    // descriptors in SGPRs (otherwise every load is wrapped in a readfirstlane loop).
+    auto uniform_ptr = [](const char* p) {
+      const uint64_t v = reinterpret_cast<uint64_t>(p);
+      const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+      const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+      return reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+    };
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(A), 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(B), 0, 0x7fffffff, 0x00020000);
     auto issue_a = [&](int ks, int slot, int part) {
       char* st = lds + slot * SLOT;
 #pragma unroll
