@@ -72,7 +72,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the target config)")
     ap.add_argument("--vocab-chunk", type=int, default=0)
-    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -200,7 +200,7 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}", "P": cfg.P, "G": cfg.G, "T": cfg.T,
                    "d": cfg.d, "V": cfg.V, "token_slots": cfg.N, "valid_tokens": nv, "loss": cfg.loss,
-                   "vocab_chunk": int(args.vocab_chunk) or 8192,
+                   "vocab_chunk": int(args.vocab_chunk) or "library default",
                    "tokens_counted": "valid (unpadded) tokens", "slots_per_s": cfg.N / (ms_per_step * 1e-3)},
         "step_tflops_executed": step_flops_hw / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_peak_executed": step_flops_hw / (ms_per_step * 1e-3) / 1e12 / peak,

@@ -70,8 +70,9 @@ typedef struct lmhead_desc {
   int32_t P, G, T;     /* R = P*G responses, N = R*T token slots                          */
   int32_t d, V;        /* hidden size (multiple of 64) and vocabulary size                */
   int32_t dtype;       /* LMHEAD_F32 or LMHEAD_BF16: storage type of H and W              */
-  int32_t vocab_chunk; /* vocabulary chunk size; 0 = library default.  Rounded up to a    */
-                       /* multiple of the 256-wide vocabulary tile.                       */
+  int32_t vocab_chunk; /* vocabulary chunk of the backward (columns of dZ held at once);  */
+                       /* 0 = library default (as wide as ~48 GB of scratch allows, at    */
+                       /* most 32768).  Rounded up to a multiple of the 256-wide tile.    */
   int32_t reserved;    /* must be 0                                                        */
   int64_t ldH, ldW;    /* row strides of H and W in elements (>= d)                       */
   uint32_t flags;      /* LMHEAD_FLAG_*                                                    */

@@ -35,8 +35,10 @@ struct WsLayout {
   int64_t Ncap;     // N rounded up to the tile
   int64_t Vp;       // V rounded up to the tile
   int64_t dp;       // d rounded up to the tile
-  int64_t Vc;       // vocabulary chunk (multiple of the tile)
+  int64_t Vc;       // vocabulary chunk of the backward (multiple of the tile)
   int64_t nchunks;  // number of vocabulary chunks
+  int64_t strip_tiles;  // vocabulary tiles that one forward workgroup walks
+  int64_t nstrips;      // forward strips = partial-statistics planes per row
   // Row pitches (elements) of the workspace matrices.  Each is its logical width plus one
   // 128-byte line: a power-of-two pitch would put every row of a tile on the same L2
   // channel and set (the token-major operands have a pitch of Ncap elements, often 2^k).
@@ -44,10 +46,21 @@ struct WsLayout {
   size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, total;
 };
 
+// Default backward chunk: as wide as keeps the two dZ copies (worst case: every slot valid)
+// within about 48 GB, at most 32768 columns.  Wider chunks mean fewer read-modify-write
+// passes over dH and longer contractions per launch.
 static inline int64_t default_vocab_chunk(const lmhead_desc* d) {
-  (void)d;
-  return 8192;
+  const int64_t esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
+  const int64_t N = (int64_t)d->P * d->G * d->T;
+  int64_t vc = (48ll << 30) / (2 * esz * (N > 0 ? N : 1));
+  vc = vc / kTile * kTile;
+  if (vc > 32768) vc = 32768;
+  if (vc < 4 * kTile) vc = 4 * kTile;
+  return vc;
 }
+// Forward strips are short: short-lived workgroups are dispatched in tile-walk order, which
+// keeps the workgroups that share operand slabs in step with each other.
+constexpr int kFwdStripTiles = 4;
 
 static inline WsLayout make_layout(const lmhead_desc* d) {
   WsLayout L{};
@@ -62,6 +75,8 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   if (vc > L.Vp) vc = L.Vp;
   L.Vc = vc;
   L.nchunks = (L.Vp + vc - 1) / vc;
+  L.strip_tiles = kFwdStripTiles;
+  L.nstrips = (L.Vp / kTile + L.strip_tiles - 1) / L.strip_tiles;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -75,7 +90,7 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   L.g_c = take((size_t)L.Ncap * 4);
   L.lse_c = take((size_t)L.Ncap * 4);
   L.zy = take((size_t)L.Ncap * 4);
-  L.part = take((size_t)3 * L.nchunks * L.Ncap * 4);
+  L.part = take((size_t)3 * L.nstrips * L.Ncap * 4);
   const int64_t pad = 128 / L.esz;
   L.ldHc = d->d + pad;
   L.ldHcT = L.Ncap + pad;
@@ -117,8 +132,8 @@ struct FwdArgs {
   int64_t ldW;
   int d, V;
   int64_t Ncap;
-  int tiles_per_chunk; // vocabulary tiles each workgroup walks
-  int nchunks;
+  int tiles_per_chunk; // vocabulary tiles each workgroup walks (one strip)
+  int nchunks;         // number of strips
   const int32_t* tok_c;
   const WsHeader* hdr;
   float* part;         // [3][nchunks][Ncap]
