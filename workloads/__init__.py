@@ -20,6 +20,8 @@ from .gen import (
     weight,
     perturbed_weight,
     sample_valid_rows,
+    synthetic_logprobs,
+    synthetic_upstream_grad,
     STREAM_H,
     STREAM_W,
     STREAM_W_OLD,
@@ -31,6 +33,6 @@ __all__ = [
     "bf16_bits_from_f32", "f32_from_bf16_bits", "as_f64",
     "lengths", "rewards", "log_z", "tokens",
     "matrix", "matrix_rows", "hidden", "weight", "perturbed_weight",
-    "sample_valid_rows",
+    "sample_valid_rows", "synthetic_logprobs", "synthetic_upstream_grad",
     "STREAM_H", "STREAM_W", "STREAM_W_OLD", "STREAM_W_REF",
 ]

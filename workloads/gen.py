@@ -232,3 +232,36 @@ def sample_valid_rows(cfg: Workload, lens: np.ndarray, tok: np.ndarray, count: i
     if need > 0:
         got = np.concatenate([got, rng.choice(rest, size=need, replace=False)])
     return np.sort(got)[:count].astype(np.int64)
+
+
+# ---------------------------------------------------------------------------
+# synthetic stand-ins for intermediate tensors (full-size checks of single stages)
+# ---------------------------------------------------------------------------
+
+STREAM_SYN_LOGP = 10
+STREAM_SYN_GRAD = 11
+
+
+def synthetic_logprobs(cfg: Workload):
+    """Seeded stand-ins for (logp, logp_old, logp_ref), float32[N] each.
+
+    Values have the scale of real token log-probs (about -ln V with a spread), the old policy
+    is a small perturbation of the current one (so both clip branches occur) and the reference
+    a larger one.  Used to check the O(N) loss kernels at full size without first running
+    the vocabulary-sized forward in the oracle.
+    """
+    rng = _rng(cfg, STREAM_SYN_LOGP)
+    base = -np.abs(rng.standard_normal(cfg.N)) * 2.0 - 0.5 * np.log(cfg.V)
+    old = base + rng.standard_normal(cfg.N) * 0.15
+    ref = base + rng.standard_normal(cfg.N) * 0.5
+    return base.astype(np.float32), old.astype(np.float32), ref.astype(np.float32)
+
+
+def synthetic_upstream_grad(cfg: Workload, lens: np.ndarray) -> np.ndarray:
+    """Seeded stand-in for dL/dlogp, float32[N]: N(0,1)/(R*len_r) on valid slots, 0 on padding."""
+    rng = _rng(cfg, STREAM_SYN_GRAD)
+    g = rng.standard_normal((cfg.R, cfg.T)).astype(np.float32)
+    t = np.arange(cfg.T)[None, :]
+    ln = np.asarray(lens, dtype=np.int64)[:, None]
+    w = np.where(t < ln, 1.0 / (cfg.R * np.maximum(ln, 1)), 0.0)
+    return (g * w).astype(np.float32).reshape(cfg.N)
