@@ -1,0 +1,122 @@
+"""CPU-only checks of the host side of the library: the shared object loads and exports every
+symbol the header declares, argument validation returns the documented codes before anything
+is launched, workspace sizing behaves, and the tile-walk mapping is a bijection."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+import paper_2603_04411_amd as L
+from paper_2603_04411_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(L.library_path()):
+        from paper_2603_04411_amd.build import build_library
+        build_library()
+    return L.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "lmhead.h")).read()
+    declared = re.findall(r"LMHEAD_API\s+[\w\s\*]+?\b(\w+)\s*\(", header)
+    assert len(declared) >= 12
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in lmhead.h but not exported"
+    assert sorted(declared) == sorted(L.EXPORTED_SYMBOLS)
+    assert lib.lmhead_abi_version() == 1
+    # nothing but the C ABI is exported
+    out = subprocess.run(["nm", "-D", "--defined-only", L.library_path()], capture_output=True, text=True).stdout
+    exported = [ln.split()[-1] for ln in out.splitlines() if " T " in ln]
+    assert sorted(exported) == sorted(declared)
+
+
+def test_descriptor_matches_c_layout():
+    # int32 x8, int64 x2, uint32 x2 with natural alignment
+    assert C.sizeof(B.LmheadDesc) == 8 * 4 + 2 * 8 + 2 * 4
+    assert B.LmheadDesc.ldH.offset == 32 and B.LmheadDesc.flags.offset == 48
+
+
+def test_descriptor_validation_codes(lib):
+    ok = L.make_desc(2, 4, 32, 256, 4096, "f32")
+    assert L.validate_desc(ok) == 0 and L.workspace_bytes(ok) > 0
+    cases = [
+        (dict(P=0), -2), (dict(T=-1), -2), (dict(V=0), -2), (dict(d=250), -2), (dict(d=0), -2),
+        (dict(ldH=128), -2), (dict(ldW=255), -2), (dict(dtype=7), -3), (dict(flags=1 << 9), -3),
+        (dict(vocab_chunk=-5), -2), (dict(P=70000, G=70000), -2), (dict(ldH=258), -4),
+    ]
+    for change, code in cases:
+        kw = dict(P=2, G=4, T=32, d=256, V=4096, dtype="f32")
+        kw.update(change)
+        desc = L.make_desc(**kw)
+        assert L.validate_desc(desc) == code, (change, L.validate_desc(desc))
+        assert L.workspace_bytes(desc) == 0
+    assert lib.lmhead_validate_desc(None) == -1
+
+
+def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
+    desc = L.make_desc(2, 4, 32, 256, 4096, "bf16")
+    need = L.workspace_bytes(desc)
+    p = 0x10000   # never dereferenced: every call below must fail in host-side validation
+    d = C.byref(desc)
+    fwd, bwd = lib.lmhead_logprob_fwd, lib.lmhead_logprob_bwd
+    assert fwd(d, None, p, p, p, p, p, None, None, None, p, need, None) == -1
+    assert fwd(d, p, p, p, p, None, p, None, None, None, p, need, None) == -1
+    assert fwd(d, p, p, p, p, p, p, None, None, None, None, need, None) == -1
+    assert fwd(d, p + 8, p, p, p, p, p, None, None, None, p, need, None) == -4
+    assert fwd(d, p, p, p, p, p, p, None, None, None, p + 64, need, None) == -4
+    assert fwd(d, p, p, p, p, p, p, None, None, None, p, need - 1, None) == -5
+    assert bwd(d, p, p, p, p, None, p, p, p, p, need, None) == -1
+    assert bwd(d, p, p, p, p, p, p, p + 4, p, p, need, None) == -4
+    assert bwd(d, p, p, p, p, p, p, p, p, p, 0, None) == -5
+    bad = L.make_desc(2, 4, 32, 100, 4096, "bf16")
+    assert fwd(C.byref(bad), p, p, p, p, p, p, None, None, None, p, 1 << 40, None) == -2
+    assert lib.group_advantage(None, 2, 4, 1e-6, 0, p, None) == -1
+    assert lib.group_advantage(p, 0, 4, 1e-6, 0, p, None) == -2
+    assert lib.group_advantage(p, 2, 4, 1e-6, 2, p, None) == -2
+    lws = L.loss_workspace_bytes(2, 4, 32)
+    assert lws > 0 and L.loss_workspace_bytes(0, 4, 32) == 0
+    g = lib.grpo_loss
+    assert g(p, p, None, p, p, 2, 4, 32, 0.2, 0.2, 0.04, 0, None, p, None, p, lws, None) == -1
+    assert g(p, p, None, p, p, 2, 4, 32, 0.2, 0.2, 0.04, 3, p, p, None, p, lws, None) == -2
+    assert g(p, p, None, p, p, 2, 4, 32, 0.2, 0.2, 0.04, 0, p, p, None, p, lws - 1, None) == -5
+    f = lib.flowrl_tb_loss
+    assert f(p, None, p, p, p, 2, 4, 32, 1.0, p, p, None, None, p, lws, None) == -1
+    assert f(p, p, p, p, p, 2, 4, -32, 1.0, p, p, None, None, p, lws, None) == -2
+    assert f(p, p, p, p, p, 2, 4, 32, 1.0, p, p, None, None, p, 8, None) == -5
+    assert lib.lmhead_check(None, None) == -1
+    ms, n = C.c_double(), C.c_int64()
+    assert lib.lmhead_timing_read(9, C.byref(ms), C.byref(n)) == -2
+    assert lib.lmhead_timing_read(0, None, C.byref(n)) == -1
+
+
+def test_workspace_grows_with_the_problem_and_default_chunk_is_bounded():
+    small = L.workspace_bytes(L.make_desc(8, 8, 256, 2048, 151936, "bf16"))
+    big = L.workspace_bytes(L.make_desc(32, 8, 2048, 4096, 151936, "bf16"))
+    huge = L.workspace_bytes(L.make_desc(8, 16, 8192, 5120, 151936, "bf16"))
+    assert small < big < huge < 100 * 2 ** 30          # sized for a 288 GB part, well below it
+    narrow = L.workspace_bytes(L.make_desc(32, 8, 2048, 4096, 151936, "bf16", vocab_chunk=2048))
+    assert narrow < big
+
+
+def test_binding_has_no_cpu_fallback():
+    import torch
+    desc = L.make_desc(1, 1, 8, 64, 100, "bf16")
+    t = torch.zeros(8, 64)
+    with pytest.raises(ValueError):
+        L.lmhead_logprob_fwd(desc, t, t, t, t, t, t, None, None, None, t)
+
+
+def test_tile_walk_is_a_bijection(tmp_path):
+    exe = tmp_path / "tile_map_check"
+    src = os.path.join(ROOT, "tests", "host", "tile_map_check.cpp")
+    subprocess.run(["g++", "-O2", "-o", str(exe), src], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "bad=0" in r.stdout
