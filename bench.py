@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the target config)")
     ap.add_argument("--vocab-chunk", type=int, default=0)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device-to-device copy first (reference point for FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -140,6 +142,13 @@ def main() -> int:
                              g_logZ, None, loss_ws)
         L.lmhead_logprob_bwd(desc, H, W, tok_d, lens_d, lse, g_logp, dH, dW, ws)
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not cfg.recompute_old_ref:
         fwd_other()      # old / reference log-probs are inputs of the step here: computed once, untimed
     torch.cuda.synchronize()

@@ -108,9 +108,11 @@ struct GemmTile {
   __device__ static inline int wave_m() { return wave() % WGM; }
   __device__ static inline int wave_n() { return wave() / WGM; }
   // Tile-relative coordinates of accumulator element v of block (i, j).
-  __device__ static inline int m_of(int i, int v) {
-    return wave_m() * WM + i * 32 + 8 * (v >> 2) + 4 * (lane() >> 5) + (v & 3);
-  }
+  __device__ static inline int m_of(int i, int v) { return m_base() + m_const(i, v); }
+  // m_of split into its lane-dependent part and a compile-time constant, so that comparisons
+  // against it can be written with immediates instead of one live register per (i, v)
+  __device__ static inline int m_base() { return wave_m() * WM + 4 * (lane() >> 5); }
+  __device__ static constexpr int m_const(int i, int v) { return i * 32 + 8 * (v >> 2) + (v & 3); }
   __device__ static inline int n_of(int j) { return wave_n() * WN + j * 32 + (lane() & 31); }
 
   __device__ static inline int swz(int r) { return (r ^ (r >> 3)) & 7; }

@@ -9,6 +9,8 @@
 // and 16*TM vocabulary entries of it, so the softmax statistics are reduced inside the lane
 // and need a single cross-lane step per chunk; and a lane's four consecutive M entries are
 // contiguous in the row-major outputs (dZ row, dH row, dW row).
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_core.h"
 
@@ -100,62 +102,59 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     if (__any(hit)) {
 #pragma unroll
       for (int j = 0; j < G::TN; ++j) {
-        const int rel = tokj[j] - m0;
+        const int rel = tokj[j] - m0 - G::m_base();   // compared with compile-time constants
+        float zsel = 0.f;
+        bool found = false;
 #pragma unroll
         for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (G::m_of(i, v) == rel) a.zy[n0 + G::n_of(j)] = acc[i][j][v];
+          for (int v = 0; v < 16; ++v) {
+            const bool eq = rel == G::m_const(i, v);
+            zsel = eq ? acc[i][j][v] : zsel;
+            found |= eq;
+          }
+        if (found) a.zy[n0 + G::n_of(j)] = zsel;
       }
     }
 
-    // online softmax statistics, inside the lane
-    const bool full = m0 + G::BM <= a.V;
+    // online softmax statistics, inside the lane, one 32x32 block (16 values of one token
+    // column) at a time; the scheduling barrier after each block keeps the accumulator reads of
+    // later blocks from being hoisted, so only 16 values are live in VGPRs at a time
+    const int vlim = a.V - m0 - G::m_base();   // vocabulary rows with m_const >= vlim are padding
+    auto block_stats = [&](auto full_tag, const f32x16_t& blk, int i, float& m_run, float& s_run, float& t_run) {
+      constexpr bool kFull = decltype(full_tag)::value;
+      float z[16];
 #pragma unroll
-    for (int j = 0; j < G::TN; ++j) {
-      float tmax = kNegInf;
-      if (full) {
+      for (int v = 0; v < 16; ++v) z[v] = (kFull || G::m_const(i, v) < vlim) ? blk[v] : kNegInf;
+      float tmax = fmaxf(z[0], z[1]);
 #pragma unroll
-        for (int i = 0; i < G::TM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, acc[i][j][v]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < G::TM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            tmax = fmaxf(tmax, (m0 + G::m_of(i, v) < a.V) ? acc[i][j][v] : kNegInf);
-      }
-      const float mn = fmaxf(mr[j], tmax);
+      for (int v = 2; v < 16; v += 2) tmax = fmaxf(tmax, fmaxf(z[v], z[v + 1]));
+      const float mn = fmaxf(m_run, tmax);
       const float ms = (mn == kNegInf) ? 0.f : mn;
-      const float sc = fast_exp2((mr[j] - ms) * kLog2e);
+      const float sc = fast_exp2((m_run - ms) * kLog2e);
       const float bias = -ms * kLog2e;
       float ss = 0.f, ts = 0.f;
-      if (full) {
 #pragma unroll
-        for (int i = 0; i < G::TM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float z = acc[i][j][v];
-            const float e = fast_exp2(fmaf(z, kLog2e, bias));
-            ss += e;
-            ts = fmaf(e, z, ts);
-          }
-      } else {
-#pragma unroll
-        for (int i = 0; i < G::TM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const bool ok = m0 + G::m_of(i, v) < a.V;
-            const float z = ok ? acc[i][j][v] : 0.f;
-            const float e = ok ? fast_exp2(fmaf(z, kLog2e, bias)) : 0.f;
-            ss += e;
-            ts = fmaf(e, z, ts);
-          }
+      for (int v = 0; v < 16; ++v) {
+        const float e = fast_exp2(fmaf(z[v], kLog2e, bias));   // exp2(-inf) = 0 on padding rows
+        ss += e;
+        ts = fmaf(e, (kFull || G::m_const(i, v) < vlim) ? z[v] : 0.f, ts);
       }
-      sr[j] = fmaf(sr[j], sc, ss);
-      tr[j] = fmaf(tr[j], sc, ts);
-      mr[j] = mn;
+      s_run = fmaf(s_run, sc, ss);
+      t_run = fmaf(t_run, sc, ts);
+      m_run = mn;
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    if (m0 + G::BM <= a.V) {
+#pragma unroll
+      for (int j = 0; j < G::TN; ++j)
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i) block_stats(std::true_type{}, acc[i][j], i, mr[j], sr[j], tr[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < G::TN; ++j)
+#pragma unroll
+        for (int i = 0; i < G::TM; ++i) block_stats(std::false_type{}, acc[i][j], i, mr[j], sr[j], tr[j]);
     }
   }
 
@@ -253,7 +252,8 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
     const int64_t n = n0 + G::n_of(j);
     const float g = a.g_c[n];
     const float bias = -a.lse_c[n] * kLog2e;
-    const int rel = a.tok_c[n] - m0;
+    const int rel = a.tok_c[n] - m0 - G::m_base();   // compared with compile-time constants
+    const int vlim = a.V - m0 - G::m_base();
 #pragma unroll
     for (int i = 0; i < G::TM; ++i)
 #pragma unroll
@@ -263,8 +263,8 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kLog2e, bias));
-          const float oh = (mt + e == rel) ? 1.f : 0.f;
-          dz[e] = (m0 + mt + e < a.V) ? g * (oh - p) : 0.f;
+          const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
+          dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
         }
         const int64_t mc = mrel0 + mt;
         Store4<E>::row(dZ + ((size_t)n * a.ldZ + mc) * Elem<E>::size, dz[0], dz[1], dz[2], dz[3]);
