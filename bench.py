@@ -40,6 +40,23 @@ def to_device(a: np.ndarray):
     return torch.from_numpy(a).cuda()
 
 
+TRAFFIC_KEYS = ["fwd_kernel", "dz_kernel", "gemm_t_kernel<dH>", "gemm_t_kernel<dW>"]
+
+
+def recorded_traffic(kind: int):
+    """HBM-side bytes per launch of one kernel kind for configs[2] at the default chunking, as recorded
+    from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; scaling stated in the file).  None if absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_config2.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == TRAFFIC_KEYS[kind]:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, H_host, W_host, tok, lens, sample_rows: int, gpu_logp=None):
     """Times the oracle (as it stands) on a seeded subset of valid rows: fwd + CE-style bwd."""
     import workloads as wl
@@ -189,7 +206,8 @@ def main() -> int:
     flops_per_launch = flops_per_pass * dom_passes / dn
     achieved = flops_per_launch / (dms / dn * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom], "achieved": achieved, "peak": peak,
-                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": recorded_traffic(dom) if (cfg.index == 2 and not args.vocab_chunk) else None,
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": dms / dn}
     step_flops_hw = flops_per_pass * (3 + n_fwd_passes)       # executed, including the dZ recompute
     step_flops_model = flops_per_pass * 3                      # logits + dH + dW
