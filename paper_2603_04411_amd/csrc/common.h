@@ -37,8 +37,7 @@ struct WsLayout {
   int64_t dp;       // d rounded up to the tile
   int64_t Vc;       // vocabulary chunk of the backward (multiple of the tile)
   int64_t nchunks;  // number of vocabulary chunks
-  int64_t strip_tiles;  // vocabulary tiles that one forward workgroup walks
-  int64_t nstrips;      // forward strips = partial-statistics planes per row
+  int64_t ntiles;   // vocabulary tiles = planes of per-tile softmax statistics per row
   // Row pitches (elements) of the workspace matrices.  Each is its logical width plus one
   // 128-byte line: a power-of-two pitch would put every row of a tile on the same L2
   // channel and set (the token-major operands have a pitch of Ncap elements, often 2^k).
@@ -58,9 +57,7 @@ static inline int64_t default_vocab_chunk(const lmhead_desc* d) {
   if (vc < 4 * kTile) vc = 4 * kTile;
   return vc;
 }
-// Forward strips are short: short-lived workgroups are dispatched in tile-walk order, which
-// keeps the workgroups that share operand slabs in step with each other.
-constexpr int kFwdStripTiles = 4;
+
 
 static inline WsLayout make_layout(const lmhead_desc* d) {
   WsLayout L{};
@@ -75,8 +72,7 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   if (vc > L.Vp) vc = L.Vp;
   L.Vc = vc;
   L.nchunks = (L.Vp + vc - 1) / vc;
-  L.strip_tiles = kFwdStripTiles;
-  L.nstrips = (L.Vp / kTile + L.strip_tiles - 1) / L.strip_tiles;
+  L.ntiles = L.Vp / kTile;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -90,7 +86,7 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   L.g_c = take((size_t)L.Ncap * 4);
   L.lse_c = take((size_t)L.Ncap * 4);
   L.zy = take((size_t)L.Ncap * 4);
-  L.part = take((size_t)3 * L.nstrips * L.Ncap * 4);
+  L.part = take((size_t)3 * L.ntiles * L.Ncap * 4);
   const int64_t pad = 128 / L.esz;
   L.ldHc = d->d + pad;
   L.ldHcT = L.Ncap + pad;
@@ -132,17 +128,16 @@ struct FwdArgs {
   int64_t ldW;
   int d, V;
   int64_t Ncap;
-  int tiles_per_chunk; // vocabulary tiles each workgroup walks (one strip)
-  int nchunks;         // number of strips
+  int ntiles;          // vocabulary tiles (one per workgroup)
   const int32_t* tok_c;
   const WsHeader* hdr;
-  float* part;         // [3][nchunks][Ncap]
+  float* part;         // [3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
   float* zy;           // [Ncap]
 };
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s);
 
-// Merges the per-chunk partials and scatters logp / lse / entropy to slot order (0 on padding).
-hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int64_t Ncap,
+// Merges the per-tile partials and scatters logp / lse / entropy to slot order (0 on padding).
+hipError_t launch_finalize(const float* part, const float* zy, int ntiles, int64_t Ncap,
                            const int32_t* len, const int32_t* cu_len, int R, int T, float* logp,
                            float* lse, float* entropy, hipStream_t s);
 

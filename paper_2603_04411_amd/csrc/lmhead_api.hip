@@ -118,8 +118,7 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
   fa.d = desc->d;
   fa.V = desc->V;
   fa.Ncap = L.Ncap;
-  fa.tiles_per_chunk = (int)L.strip_tiles;
-  fa.nchunks = (int)L.nstrips;
+  fa.ntiles = (int)L.ntiles;
   fa.tok_c = w.at<int32_t>(L.tok_c);
   fa.hdr = hdr;
   fa.part = w.at<float>(L.part);
@@ -128,7 +127,7 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
     TimedLaunch tl(0, s);
     LM_TRY(launch_fwd(desc->dtype, fa, s));
   }
-  LM_TRY(launch_finalize(w.at<float>(L.part), w.at<float>(L.zy), (int)L.nstrips, L.Ncap, len,
+  LM_TRY(launch_finalize(w.at<float>(L.part), w.at<float>(L.zy), (int)L.ntiles, L.Ncap, len,
                          w.at<int32_t>(L.cu_len), (int)L.R, desc->T, logp, lse, entropy, s));
   return LMHEAD_OK;
 }

@@ -1,5 +1,5 @@
 // The three MFMA kernels of the library, all built on GemmTile (gemm_core.h):
-//   fwd_kernel    logits tile (vocabulary x tokens) -> online max / sum-exp / sum-exp*z per token,
+//   fwd_kernel    logits tile (vocabulary x tokens) -> max / sum-exp / sum-exp*z per token and tile,
 //                 target-logit capture; nothing of the tile is stored           (log-softmax of L_CE, Eq. 9)
 //   dz_kernel     logits tile recomputed -> dZ = g (onehot - softmax), stored in both orientations
 //   gemm_t_kernel plain contraction with a transposed, row-mapped fp32 store    (dH and dW)
@@ -7,7 +7,7 @@
 // Orientation: the vocabulary (or d) runs along the MFMA M axis and tokens (or vocabulary
 // rows of dW) along N.  With the 32x32 accumulator layout a lane then owns ONE token column
 // and 16*TM vocabulary entries of it, so the softmax statistics are reduced inside the lane
-// and need a single cross-lane step per chunk; and a lane's four consecutive M entries are
+// and need a single cross-lane step per tile; and a lane's four consecutive M entries are
 // contiguous in the row-major outputs (dZ row, dH row, dW row).
 #include <type_traits>
 
@@ -50,76 +50,72 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int nblk = (nv + G::BN - 1) / G::BN;
-  int chunk, nb;
-  if (!xcd_tile_coords(blockIdx.x, a.nchunks, nblk, kMapBx, kMapBy, chunk, nb)) return;
+  // one vocabulary tile x one token block per workgroup: short-lived workgroups are dispatched in
+  // tile-walk order, which keeps the ones that share operand slabs in step with each other
+  int tile, nb;
+  if (!xcd_tile_coords(blockIdx.x, a.ntiles, nblk, kMapBx, kMapBy, tile, nb)) return;
   const int64_t n0 = (int64_t)nb * G::BN;
-  const int total_tiles = (a.V + G::BM - 1) / G::BM;
-  const int t_lo = chunk * a.tiles_per_chunk;
-  const int t_hi = min(t_lo + a.tiles_per_chunk, total_tiles);
+  const int m0 = tile * G::BM;
   const int ksteps = a.d * Elem<E>::size / G::KB;
   const int64_t pitchH = a.ldHc * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
-  const char* Hc = static_cast<const char*>(a.Hc) + n0 * pitchH;
-  const char* W = static_cast<const char*>(a.W);
 
-  uint32_t offB[G::B_LD];
+  uint32_t offA[G::A_LD], offB[G::B_LD];
+#pragma unroll
+  for (int q = 0; q < G::A_LD; ++q) {
+    const int row = G::ldA_row(q);
+    offA[q] = (uint32_t)((min(m0 + row, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
+  }
 #pragma unroll
   for (int q = 0; q < G::B_LD; ++q) {
     const int row = G::ldB_row(q);
     offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
   }
+  typename G::Acc acc;
+  G::zero(acc);
+  G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
+         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
 
-  int tokj[G::TN];
   float mr[G::TN], sr[G::TN], tr[G::TN];
 #pragma unroll
   for (int j = 0; j < G::TN; ++j) {
-    tokj[j] = a.tok_c[n0 + G::n_of(j)];
     mr[j] = kNegInf;
     sr[j] = 0.f;
     tr[j] = 0.f;
   }
 
-  for (int tile = t_lo; tile < t_hi; ++tile) {
-    const int m0 = tile * G::BM;
-    uint32_t offA[G::A_LD];
-#pragma unroll
-    for (int q = 0; q < G::A_LD; ++q) {
-      const int row = G::ldA_row(q);
-      offA[q] = (uint32_t)((min(m0 + row, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
-    }
-    typename G::Acc acc;
-    G::zero(acc);
-    G::run(acc, W + (int64_t)m0 * pitchW, offA, Hc, offB, ksteps, smem);
-
-#ifdef LMHEAD_DBG_SKIP_EPILOGUE
-    if (acc[0][0][0] == 12345.f) mr[0] = acc[1][1][3];
-    continue;
-#endif
-    // target-logit capture: only where some lane's target falls inside this tile
+  // target-logit capture: only where some lane's target falls inside this tile
+  {
+    int relj[G::TN];
     bool hit = false;
 #pragma unroll
-    for (int j = 0; j < G::TN; ++j) hit |= (tokj[j] >= m0) & (tokj[j] < m0 + G::BM);
+    for (int j = 0; j < G::TN; ++j) {
+      const int tk = a.tok_c[n0 + G::n_of(j)];
+      hit |= (tk >= m0) & (tk < m0 + G::BM);
+      relj[j] = tk - m0 - G::m_base();   // compared with compile-time constants
+    }
     if (__any(hit)) {
 #pragma unroll
       for (int j = 0; j < G::TN; ++j) {
-        const int rel = tokj[j] - m0 - G::m_base();   // compared with compile-time constants
         float zsel = 0.f;
         bool found = false;
 #pragma unroll
         for (int i = 0; i < G::TM; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const bool eq = rel == G::m_const(i, v);
+            const bool eq = relj[j] == G::m_const(i, v);
             zsel = eq ? acc[i][j][v] : zsel;
             found |= eq;
           }
         if (found) a.zy[n0 + G::n_of(j)] = zsel;
       }
     }
+  }
 
-    // online softmax statistics, inside the lane, one 32x32 block (16 values of one token
-    // column) at a time; the scheduling barrier after each block keeps the accumulator reads of
-    // later blocks from being hoisted, so only 16 values are live in VGPRs at a time
+  // softmax statistics of this tile, inside the lane, one 32x32 block (16 values of one token
+  // column) at a time; the scheduling barrier after each block keeps the accumulator reads of
+  // later blocks from being hoisted, so only 16 values are live in VGPRs at a time
+  {
     const int vlim = a.V - m0 - G::m_base();   // vocabulary rows with m_const >= vlim are padding
     auto block_stats = [&](auto full_tag, const f32x16_t& blk, int i, float& m_run, float& s_run, float& t_run) {
       constexpr bool kFull = decltype(full_tag)::value;
@@ -181,8 +177,8 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       const float* q = red + ((size_t)w * G::BN + n) * 3;
       merge_stats(m, s, t, q[0], q[1], q[2]);
     }
-    const size_t base = (size_t)chunk * a.Ncap + n0 + n;
-    const size_t plane = (size_t)a.nchunks * a.Ncap;
+    const size_t base = (size_t)tile * a.Ncap + n0 + n;
+    const size_t plane = (size_t)a.ntiles * a.Ncap;
     a.part[base] = m;
     a.part[plane + base] = s;
     a.part[2 * plane + base] = t;
@@ -345,7 +341,7 @@ hipError_t allow_lds(K kernel, int bytes) {
 }  // namespace
 
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s) {
-  const dim3 grid(xcd_grid_size(a.nchunks, a.Ncap / kTile, kMapBy));
+  const dim3 grid(xcd_grid_size(a.ntiles, a.Ncap / kTile, kMapBy));
   hipError_t e;
   if (dtype == LMHEAD_BF16) {
     using G = Tile<bf16_tag>;
