@@ -245,31 +245,78 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   if (acc[0][0][0] == 12345.f) dZ[0] = 1;
   return;
 #endif
+  // The tile leaves through LDS so that both copies are written with full 16-byte-per-lane,
+  // line-contiguous stores: registers hold 4 consecutive vocabulary entries of one token, which
+  // is neither orientation's row.  JG of the wave's TN token blocks are staged per phase (as many
+  // as fit next to each other in LDS in both orientations).
+  constexpr int ESZ = Elem<E>::size;
+  constexpr int JG = ESZ == 2 ? 2 : 1;            // token blocks (of 32) per wave per phase
+  constexpr int NTOK = G::WGN * JG * 32;          // tokens staged per phase
+  constexpr int P1 = G::BM * ESZ + 16;            // pitch of the [token][vocab] staging rows
+  constexpr int P2 = NTOK * ESZ + 16;             // pitch of the [vocab][token] staging rows
+  constexpr int L2_OFF = NTOK * P1;
+  static_assert(L2_OFF + G::BM * P2 <= G::LDS_BYTES, "both staging layouts fit in LDS");
+  static_assert(G::TN % JG == 0, "phases cover the wave tile evenly");
+  char* st1 = smem;
+  char* st2 = smem + L2_OFF;
+  const int vlim = a.V - m0 - G::m_base();
 #pragma unroll
-  for (int j = 0; j < G::TN; ++j) {
-    const int64_t n = n0 + G::n_of(j);
-    const float g = a.g_c[n];
-    const float bias = -a.lse_c[n] * kLog2e;
-    const int rel = a.tok_c[n] - m0 - G::m_base();   // compared with compile-time constants
-    const int vlim = a.V - m0 - G::m_base();
+  for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
-    for (int i = 0; i < G::TM; ++i)
+    for (int jj = 0; jj < JG; ++jj) {
+      const int j = jg * JG + jj;
+      const int64_t n = n0 + G::n_of(j);
+      const float g = a.g_c[n];
+      const float bias = -a.lse_c[n] * kLog2e;
+      const int rel = a.tok_c[n] - m0 - G::m_base();   // compared with compile-time constants
+      const int tl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);   // token within the phase
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float dz[4];
-        const int mt = G::m_of(i, 4 * q);  // tile-relative, multiple of 4
+      for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kLog2e, bias));
-          const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
-          dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
+        for (int q = 0; q < 4; ++q) {
+          float dz[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kLog2e, bias));
+            const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
+            dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
+          }
+          const int mt = G::m_of(i, 4 * q);   // tile-relative vocabulary row, multiple of 4
+          Store4<E>::row(st1 + tl * P1 + mt * ESZ, dz[0], dz[1], dz[2], dz[3]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) Store4<E>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
         }
-        const int64_t mc = mrel0 + mt;
-        Store4<E>::row(dZ + ((size_t)n * a.ldZ + mc) * Elem<E>::size, dz[0], dz[1], dz[2], dz[3]);
+    }
+    __syncthreads();
+    // [token][vocab] rows -> dZ: one staged row is BM*ESZ contiguous bytes of a dZ row
+    {
+      constexpr int CPR = G::BM * ESZ / 16;   // 16-byte chunks per row
+      constexpr int RPP = G::NT / CPR;        // rows per pass
+      const int c = threadIdx.x % CPR;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          Store4<E>::one(dZT + ((size_t)(mc + e) * a.ldZT + n) * Elem<E>::size, dz[e]);
+      for (int r0 = 0; r0 < NTOK; r0 += RPP) {
+        const int tl = r0 + threadIdx.x / CPR;
+        const int nl = (tl / (JG * 32)) * G::WN + jg * (JG * 32) + tl % (JG * 32);   // token within the tile
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(st1 + tl * P1 + c * 16);
+        *reinterpret_cast<u32x4_t*>(dZ + ((size_t)(n0 + nl) * a.ldZ + mrel0) * ESZ + c * 16) = v;
       }
+    }
+    // [vocab][token] rows -> dZT: a staged row holds WGN runs of JG*32 consecutive tokens
+    {
+      constexpr int CPR = NTOK * ESZ / 16;
+      constexpr int RPP = G::NT / CPR;
+      constexpr int TPC = 16 / ESZ;           // tokens per 16-byte chunk
+      const int c = threadIdx.x % CPR;
+      const int tl = c * TPC;
+      const int nl = (tl / (JG * 32)) * G::WN + jg * (JG * 32) + tl % (JG * 32);
+#pragma unroll
+      for (int r0 = 0; r0 < G::BM; r0 += RPP) {
+        const int m = r0 + threadIdx.x / CPR;
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(st2 + m * P2 + c * 16);
+        *reinterpret_cast<u32x4_t*>(dZT + ((size_t)(mrel0 + m) * a.ldZT + n0 + nl) * ESZ) = v;
+      }
+    }
+    if (jg + 1 < G::TN / JG) __syncthreads();
   }
 }
 
