@@ -360,24 +360,43 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   return;
 #endif
 
+  // The fp32 tile leaves through LDS as [n][m] rows, so that each output row segment (BM floats
+  // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.
+  constexpr int JG = 2;                           // column blocks (of 32) per wave per phase
+  constexpr int NCOL = G::WGN * JG * 32;          // tile columns (n) staged per phase
+  constexpr int P = G::BM * 4 + 16;               // staging row pitch in bytes
+  static_assert(NCOL * P <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
+  static_assert(G::BM * 4 / 16 == 64, "one staged row is one wavefront store");
 #pragma unroll
-  for (int j = 0; j < G::TN; ++j) {
-    const int64_t n = n0 + G::n_of(j);
-    if (n >= n_lim) continue;
-    const int64_t row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
-    if (row < 0) continue;
-    float* orow = a.out + row * a.ldo;
+  for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
-    for (int i = 0; i < G::TM; ++i)
+    for (int jj = 0; jj < JG; ++jj) {
+      const int j = jg * JG + jj;
+      const int nl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int m = m0 + G::m_of(i, 4 * q);
-        if (m >= a.M) continue;
-        f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        f32x4_t* dst = reinterpret_cast<f32x4_t*>(orow + m);
-        if (a.accumulate) v += *dst;
-        *dst = v;
-      }
+      for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
+        }
+    }
+    __syncthreads();
+    const int c = G::lane();                      // 16-byte chunk of the row = 4 output columns
+    const int m = m0 + c * 4;
+#pragma unroll 4
+    for (int r = G::wave(); r < NCOL; r += G::NWAVES) {
+      const int nt = (r / (JG * 32)) * G::WN + jg * (JG * 32) + r % (JG * 32);   // column within the tile
+      const int64_t n = n0 + nt;
+      if (n >= n_lim) continue;
+      const int64_t row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
+      if (row < 0 || m >= a.M) continue;
+      f32x4_t v = *reinterpret_cast<const f32x4_t*>(smem + r * P + c * 16);
+      f32x4_t* dst = reinterpret_cast<f32x4_t*>(a.out + row * a.ldo + m);
+      if (a.accumulate) v += *dst;
+      *dst = v;
+    }
+    if (jg + 1 < G::TN / JG) __syncthreads();
   }
 }
 
