@@ -10,7 +10,7 @@
 // not all of it is used, so half-line steps would halve the load throughput.  Tiles go
 // from global memory straight into LDS (buffer_load_dwordx4 ... lds, no register staging).
 // LDS is a ring of five 32 KB slots, each holding one operand's tile for one K-step; the
-// units A(0) B(0) A(1) B(1) ... go round the ring, so besides the two units being
+// units A(0) B(0) A(1) B(1) ... (or B first) go round the ring, so besides the two units being
 // multiplied, three are resident or in flight.  During K-step k a wave issues the loads of
 // B(k+1) (first half of the step) and A(k+2) (second half) into the two slots that the
 // barrier ending K-step k-1 has freed, one load behind every fourth MFMA: the vector L1
@@ -38,6 +38,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "tile_map.h"
 
@@ -82,7 +84,8 @@ constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 constexpr int kWaitVm0 = wait_vm(0);
 constexpr int kWaitLgkm0 = 0xC07F;
 
-template <typename E, int BM_, int BN_, int WGM_, int WGN_>
+// kLeadB selects which operand goes first round the LDS ring (see run()).
+template <typename E, int BM_, int BN_, int WGM_, int WGN_, bool kLeadB = false>
 struct GemmTile {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
   static constexpr int NWAVES = WGM * WGN;
@@ -138,6 +141,9 @@ struct GemmTile {
   // relative to the tile's first row) * pitch + ld_byte(row).
   // `lds` must provide LDS_BYTES bytes.  Returns with every wave past a barrier and no load
   // in flight, so LDS may be reused by the caller right away.
+  // kLeadB selects which operand goes first round the ring, i.e. which one is loaded a full K-step
+  // or more ahead (the other has half a K-step to a K-step): false = A, true = B.  Give the long
+  // lead to the operand that misses L2 more often (the one fewer concurrent workgroups share).
   __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                     const char* __restrict__ B, const uint32_t (&offB)[B_LD],
                                     int ksteps, char* lds) {
@@ -236,41 +242,52 @@ struct GemmTile {
       __builtin_amdgcn_sched_barrier(0);
     };
     auto next_slot = [](int s, int by) { s += by; return s >= NSLOT ? s - NSLOT : s; };
+    // X = the operand that leads the ring, Y = the other one
+    static_assert(A_LD == B_LD, "the ring treats both operands' load counts alike");
+    auto issue_x = [&](int ks, int slot, int part) {
+      if constexpr (kLeadB) issue_b(ks, slot, part); else issue_a(ks, slot, part);
+    };
+    auto issue_y = [&](int ks, int slot, int part) {
+      if constexpr (kLeadB) issue_a(ks, slot, part); else issue_b(ks, slot, part);
+    };
+    auto frags_xy = [&](const char* cx, const char* cy, int s, int buf) {
+      if constexpr (kLeadB) read_frags(cy, cx, s, buf); else read_frags(cx, cy, s, buf);
+    };
 
     if (ksteps <= 0) return;
-    // ring state: slots of A(ks) and B(ks); unit u lives in slot u % NSLOT
+    // ring state: slots of X(ks) and Y(ks); unit u lives in slot u % NSLOT
     int sA = 0, sB = 1;
-    issue_a(0, 0, 0); issue_a(0, 0, 1);
-    issue_b(0, 1, 0); issue_b(0, 1, 1);
-    if (ksteps > 1) { issue_a(1, 2, 0); issue_a(1, 2, 1); }
+    issue_x(0, 0, 0); issue_x(0, 0, 1);
+    issue_y(0, 1, 0); issue_y(0, 1, 1);
+    if (ksteps > 1) { issue_x(1, 2, 0); issue_x(1, 2, 1); }
     if (ksteps > 1)
       __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
     else
       __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __builtin_amdgcn_s_barrier();
-    read_frags(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
+    frags_xy(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     int ks = 0;
-    // Steady state.  Entering K-step ks: A(ks), B(ks), A(ks+1) are resident or in flight; the
-    // slots of A(ks-1) and B(ks-1) are free (all waves passed the barrier after reading them).
+    // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) are resident or in flight; the
+    // slots of X(ks-1) and Y(ks-1) are free (all waves passed the barrier after reading them).
     for (; ks + 2 < ksteps; ++ks) {
       const char* ca = lds + sA * SLOT;
       const char* cb = lds + sB * SLOT;
-      const int sB1 = next_slot(sB, 2);   // slot of B(ks+1) == slot of A(ks-1)
-      const int sA1 = next_slot(sA, 2);   // slot of A(ks+1)
-      const int sA2 = next_slot(sA1, 2);  // slot of A(ks+2) == slot of B(ks-1)
-      // sub-step 0 and 1: first and second half of B(ks+1)
-      read_frags(ca, cb, 1, 1);
-      issue_b(ks + 1, sB1, 0);
+      const int sB1 = next_slot(sB, 2);   // slot of Y(ks+1) == slot of X(ks-1)
+      const int sA1 = next_slot(sA, 2);   // slot of X(ks+1)
+      const int sA2 = next_slot(sA1, 2);  // slot of X(ks+2) == slot of Y(ks-1)
+      // sub-step 0 and 1: first and second half of Y(ks+1)
+      frags_xy(ca, cb, 1, 1);
+      issue_y(ks + 1, sB1, 0);
       mma_all(0);
       sched_region(LD_REGION_B);
-      read_frags(ca, cb, 2, 0);
-      issue_b(ks + 1, sB1, 1);
+      frags_xy(ca, cb, 2, 0);
+      issue_y(ks + 1, sB1, 1);
       mma_all(1);
       sched_region(LD_REGION_B);
-      // sub-step 2: first half of A(ks+2)
-      read_frags(ca, cb, 3, 1);
-      issue_a(ks + 2, sA2, 0);
+      // sub-step 2: first half of X(ks+2)
+      frags_xy(ca, cb, 3, 1);
+      issue_x(ks + 2, sA2, 0);
       mma_all(0);
       sched_region(LD_REGION);
       // hand-over: everything but the youngest A_LD/2 loads of this wave has landed
@@ -278,10 +295,10 @@ struct GemmTile {
       __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of A(ks+2);
+      // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of X(ks+2);
       // its target slot was freed by the barrier that ended K-step ks-1, not by this one
-      read_frags(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
-      issue_a(ks + 2, sA2, 1);
+      frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+      issue_x(ks + 2, sA2, 1);
       mma_all(1);
       sched_region(LD_REGION);
       sA = sA1;
@@ -294,15 +311,15 @@ struct GemmTile {
       const int sB1 = next_slot(sB, 2);
       const int sA1 = next_slot(sA, 2);
       const bool more = ks + 1 < ksteps;
-      read_frags(ca, cb, 1, 1);
-      if (more) issue_b(ks + 1, sB1, 0);
+      frags_xy(ca, cb, 1, 1);
+      if (more) issue_y(ks + 1, sB1, 0);
       mma_all(0);
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(ca, cb, 2, 0);
-      if (more) issue_b(ks + 1, sB1, 1);
+      frags_xy(ca, cb, 2, 0);
+      if (more) issue_y(ks + 1, sB1, 1);
       mma_all(1);
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(ca, cb, 3, 1);
+      frags_xy(ca, cb, 3, 1);
       mma_all(0);
       __builtin_amdgcn_sched_barrier(0);
       if (more) {
@@ -310,7 +327,7 @@ struct GemmTile {
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+        frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
       }
       mma_all(1);
       __builtin_amdgcn_sched_barrier(0);

@@ -24,11 +24,20 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Which operand leads the LDS ring in each kernel (see GemmTile::run); true = the B side.
+// Measured on the 32x8x2048 workload: the logits kernels do best with W leading, the two
+// backward contractions with the dZ side leading.
+#ifndef LMHEAD_LEAD_FWD
+#define LMHEAD_LEAD_FWD false
+#define LMHEAD_LEAD_DZ false
+#define LMHEAD_LEAD_DH true
+#define LMHEAD_LEAD_DW true
+#endif
 #ifndef LMHEAD_WAVES_N
 #define LMHEAD_WAVES_N 2
 #endif
-template <typename E>
-using Tile = GemmTile<E, 256, 256, 2, LMHEAD_WAVES_N>;
+template <typename E, bool kLeadB = false>
+using Tile = GemmTile<E, 256, 256, 2, LMHEAD_WAVES_N, kLeadB>;
 
 // Block shape of the XCD-local tile walk (see xcd_tile_coords): 4 x 4 work items.
 constexpr int kMapBx = 4, kMapBy = 4;
@@ -48,7 +57,7 @@ __device__ inline void merge_stats(float& m, float& s, float& t, float m2, float
 
 template <typename E>
 __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
-  using G = Tile<E>;
+  using G = Tile<E, LMHEAD_LEAD_FWD>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int nblk = (nv + G::BN - 1) / G::BN;
@@ -76,7 +85,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
-         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+                                   static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
 
   float mr[G::TN], sr[G::TN], tr[G::TN];
 #pragma unroll
@@ -209,7 +218,7 @@ struct Store4<f32_tag> {
 
 template <typename E>
 __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
-  using G = Tile<E>;
+  using G = Tile<E, LMHEAD_LEAD_DZ>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int nblk = (nv + G::BN - 1) / G::BN;
@@ -237,7 +246,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
-         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+                                  static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
 
   char* dZ = static_cast<char*>(a.dZ);
   char* dZT = static_cast<char*>(a.dZT);
@@ -324,7 +333,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 // code is the same; the parameter only gives the two uses distinct kernel names in profiles.
 template <typename E, int Role>
 __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
-  using G = Tile<E>;
+  using G = Tile<E, (Role == 0 ? LMHEAD_LEAD_DH : LMHEAD_LEAD_DW)>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int64_t n_lim = a.n_from_nv ? (int64_t)nv : a.n_limit;
