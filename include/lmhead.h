@@ -160,6 +160,17 @@ LMHEAD_API int grpo_loss(const float* logp, const float* logp_old, const float* 
               void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Cross-entropy over the target tokens: the L_CE term of the paper's training objective
+ * L = L_CE + alpha R^2 (Sec. 3.3, Eq. 9), evaluated from the forward's log-probabilities:
+ *     loss = -(1/N_v) sum_{valid i} logp_i,      g_logp_i = -1/N_v on valid slots, 0 on padding.
+ * Feeding g_logp to lmhead_logprob_bwd gives dL_CE/dH and dL_CE/dW.
+ *   logp float[R*T]; len int32[R]; loss float[1] (out); g_logp float[R*T] or NULL (out).
+ * Scratch: lmhead_loss_workspace_bytes(R, 1, T).
+ */
+LMHEAD_API int ce_loss(const float* logp, const int32_t* len, int32_t R, int32_t T,
+                       float* loss, float* g_logp, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Trajectory-balance residual (problem statement).  For response r of prompt p = r / G:
  *     sbar_theta = (1/len_r) sum_{t < len_r} logp[r,t],   sbar_ref likewise (0 if len_r = 0)
  *     delta_r = logZ[p] + sbar_theta - beta reward[r] - sbar_ref

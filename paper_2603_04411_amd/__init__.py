@@ -19,6 +19,7 @@ from .binding import (
     group_advantage,
     grpo_loss,
     flowrl_tb_loss,
+    ce_loss,
     lmhead_check,
     lmhead_timing_enable,
     lmhead_timing_read,
@@ -29,5 +30,5 @@ __all__ = [
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
-    "flowrl_tb_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
+    "flowrl_tb_loss", "ce_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
 ]

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTED_SYMBOLS = [
     "lmhead_abi_version", "lmhead_workspace_bytes", "lmhead_validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage",
-    "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "lmhead_check",
+    "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "ce_loss", "lmhead_check",
     "lmhead_timing_enable", "lmhead_timing_read",
 ]
 
@@ -83,6 +83,8 @@ def load_library():
     lib.grpo_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, f32, f32, i32, vp, vp, vp, vp, sz, vp]
     lib.flowrl_tb_loss.restype = C.c_int
     lib.flowrl_tb_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.ce_loss.restype = C.c_int
+    lib.ce_loss.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.lmhead_check.restype = C.c_int
     lib.lmhead_check.argtypes = [vp, vp]
     lib.lmhead_timing_enable.restype = C.c_int
@@ -161,6 +163,12 @@ def flowrl_tb_loss(logp, logp_ref, reward, logZ, lens, P, G, T, beta, loss, g_lo
         _ptr(logp), _ptr(logp_ref), _ptr(reward), _ptr(logZ), _ptr(lens), P, G, T, beta, _ptr(loss),
         _ptr(g_logp), _ptr(g_logZ), _ptr(resid), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "flowrl_tb_loss")
+
+
+def ce_loss(logp, lens, R, T, loss, g_logp, ws) -> None:
+    rc = load_library().ce_loss(_ptr(logp), _ptr(lens), R, T, _ptr(loss), _ptr(g_logp), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream())
+    _check(rc, "ce_loss")
 
 
 def lmhead_check(ws) -> int:

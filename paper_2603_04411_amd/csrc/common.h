@@ -192,6 +192,8 @@ hipError_t launch_grpo(const float* lp, const float* lo, const float* lr, const 
                        const int32_t* len, int P, int G, int T, float clip_lo, float clip_hi,
                        float kl, int agg, float* loss, float* g, float* stats, float* ws,
                        hipStream_t s);
+hipError_t launch_ce(const float* lp, const int32_t* len, int R, int T, float* loss, float* g, float* ws,
+                     hipStream_t s);
 hipError_t launch_flowrl(const float* lp, const float* lr, const float* reward, const float* logZ,
                          const int32_t* len, int P, int G, int T, float beta, float* loss,
                          float* g, float* gz, float* resid, float* ws, hipStream_t s);

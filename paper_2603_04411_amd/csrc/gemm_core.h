@@ -185,10 +185,6 @@ struct GemmTile {
 
     u32x4_t fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* sa, const char* sb, int s, int buf) {
-#ifdef LMHEAD_UB_NO_FRAG
-      (void)sa; (void)sb; (void)s; (void)buf;
-      return;
-#endif
       const int ch = 2 * s + half;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -202,10 +198,6 @@ struct GemmTile {
       }
     };
     auto mma_all = [&](int buf) {
-#ifdef LMHEAD_UB_NO_MMA
-      (void)buf;
-      return;
-#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -263,6 +263,16 @@ int grpo_loss(const float* logp, const float* logp_old, const float* logp_ref, c
   return LMHEAD_OK;
 }
 
+int ce_loss(const float* logp, const int32_t* len, int32_t R, int32_t T, float* loss, float* g_logp,
+            void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate_pgt(R, 1, T);
+  if (rc != LMHEAD_OK) return rc;
+  if (!logp || !len || !loss || !ws) return LMHEAD_E_NULL;
+  if (ws_bytes < loss_ws_bytes(R, 1, T)) return LMHEAD_E_WORKSPACE;
+  LM_TRY(launch_ce(logp, len, R, T, loss, g_logp, static_cast<float*>(ws), static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
 int flowrl_tb_loss(const float* logp, const float* logp_ref, const float* reward, const float* logZ,
                    const int32_t* len, int32_t P, int32_t G, int32_t T, float beta, float* loss,
                    float* g_logp, float* g_logZ, float* resid, void* ws, size_t ws_bytes, void* stream) {

@@ -27,17 +27,11 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // Which operand leads the LDS ring in each kernel (see GemmTile::run); true = the B side.
 // Measured on the 32x8x2048 workload: the logits kernels do best with W leading, the two
 // backward contractions with the dZ side leading.
-#ifndef LMHEAD_LEAD_FWD
-#define LMHEAD_LEAD_FWD false
-#define LMHEAD_LEAD_DZ false
-#define LMHEAD_LEAD_DH true
-#define LMHEAD_LEAD_DW true
-#endif
-#ifndef LMHEAD_WAVES_N
-#define LMHEAD_WAVES_N 2
-#endif
+constexpr bool kLeadFwd = false, kLeadDz = false, kLeadDh = true, kLeadDw = true;
+
+// 256 x 256 workgroup tile, four wavefronts (2 x 2) of 128 x 128.
 template <typename E, bool kLeadB = false>
-using Tile = GemmTile<E, 256, 256, 2, LMHEAD_WAVES_N, kLeadB>;
+using Tile = GemmTile<E, 256, 256, 2, 2, kLeadB>;
 
 // Block shape of the XCD-local tile walk (see xcd_tile_coords): 4 x 4 work items.
 constexpr int kMapBx = 4, kMapBy = 4;
@@ -57,7 +51,7 @@ __device__ inline void merge_stats(float& m, float& s, float& t, float m2, float
 
 template <typename E>
 __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
-  using G = Tile<E, LMHEAD_LEAD_FWD>;
+  using G = Tile<E, kLeadFwd>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int nblk = (nv + G::BN - 1) / G::BN;
@@ -218,7 +212,7 @@ struct Store4<f32_tag> {
 
 template <typename E>
 __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
-  using G = Tile<E, LMHEAD_LEAD_DZ>;
+  using G = Tile<E, kLeadDz>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int nblk = (nv + G::BN - 1) / G::BN;
@@ -250,10 +244,6 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 
   char* dZ = static_cast<char*>(a.dZ);
   char* dZT = static_cast<char*>(a.dZT);
-#ifdef LMHEAD_DBG_SKIP_EPILOGUE
-  if (acc[0][0][0] == 12345.f) dZ[0] = 1;
-  return;
-#endif
   // The tile leaves through LDS so that both copies are written with full 16-byte-per-lane,
   // line-contiguous stores: registers hold 4 consecutive vocabulary entries of one token, which
   // is neither orientation's row.  JG of the wave's TN token blocks are staged per phase (as many
@@ -333,7 +323,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 // code is the same; the parameter only gives the two uses distinct kernel names in profiles.
 template <typename E, int Role>
 __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
-  using G = Tile<E, (Role == 0 ? LMHEAD_LEAD_DH : LMHEAD_LEAD_DW)>;
+  using G = Tile<E, (Role == 0 ? kLeadDh : kLeadDw)>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int64_t n_lim = a.n_from_nv ? (int64_t)nv : a.n_limit;
@@ -364,10 +354,6 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA,
          static_cast<const char*>(a.B) + n0 * pitchB, offB, ksteps, smem);
-#ifdef LMHEAD_DBG_SKIP_EPILOGUE
-  if (acc[0][0][0] == 12345.f) a.out[0] = 1;
-  return;
-#endif
 
   // The fp32 tile leaves through LDS as [n][m] rows, so that each output row segment (BM floats
   // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.

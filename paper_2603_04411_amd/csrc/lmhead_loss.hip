@@ -133,6 +133,47 @@ __global__ __launch_bounds__(256) void grpo_final_kernel(const float* __restrict
   }
 }
 
+// Cross-entropy over the valid targets: partial sums of logp per (response, block); the gradient
+// -1/N_v is written in the same pass (every block re-derives N_v from the short length vector).
+__global__ __launch_bounds__(256) void ce_kernel(const float* __restrict__ lp, const int32_t* __restrict__ len,
+                                                 int R, int T, float* __restrict__ g_out,
+                                                 float* __restrict__ ws) {
+  __shared__ float sh[4];
+  __shared__ int nv_s;
+  const int r = blockIdx.y, b = blockIdx.x, nb = gridDim.x;
+  const int n = min(max(len[r], 0), T);
+  int acc = 0;
+  for (int q = threadIdx.x; q < R; q += 256) acc += min(max(len[q], 0), T);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (threadIdx.x == 0) nv_s = 0;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) atomicAdd(&nv_s, acc);
+  __syncthreads();
+  const float gv = nv_s > 0 ? -1.f / (float)nv_s : 0.f;
+  float a = 0.f;
+  const int t0 = b * kLossSlotsPerBlock;
+  for (int t = t0 + threadIdx.x; t < min(t0 + kLossSlotsPerBlock, T); t += 256) {
+    const size_t i = (size_t)r * T + t;
+    if (t < n) a += lp[i];
+    if (g_out) g_out[i] = t < n ? gv : 0.f;
+  }
+  a = block_sum_256(a, sh);
+  if (threadIdx.x == 0) ws[(size_t)r * nb + b] = a;
+}
+
+__global__ __launch_bounds__(256) void ce_final_kernel(const float* __restrict__ ws, int nparts,
+                                                       const int32_t* __restrict__ len, int R, int T,
+                                                       float* __restrict__ loss) {
+  __shared__ float sh[4];
+  float a = 0.f, nvf = 0.f;
+  for (int q = threadIdx.x; q < nparts; q += 256) a += ws[q];
+  for (int q = threadIdx.x; q < R; q += 256) nvf += (float)min(max(len[q], 0), T);
+  a = block_sum_256(a, sh);
+  nvf = block_sum_256(nvf, sh);
+  if (threadIdx.x == 0) loss[0] = nvf > 0.f ? -a / nvf : 0.f;
+}
+
 // Trajectory balance, pass 1: per (response, block) sums of logp and logp_ref over valid slots.
 __global__ __launch_bounds__(256) void tb_sum_kernel(const float* __restrict__ lp, const float* __restrict__ lr,
                                                      const int32_t* __restrict__ len, int T,
@@ -219,6 +260,14 @@ hipError_t launch_grpo(const float* lp, const float* lo, const float* lr, const 
   hipLaunchKernelGGL(grpo_kernel, dim3(nb, R), dim3(256), 0, s, lp, lo, lr, adv, len, R, T,
                      1.f - clip_lo, 1.f + clip_hi, kl, agg, g, ws);
   hipLaunchKernelGGL(grpo_final_kernel, dim3(1), dim3(256), 0, s, ws, R * nb, len, R, T, loss, stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_ce(const float* lp, const int32_t* len, int R, int T, float* loss, float* g, float* ws,
+                     hipStream_t s) {
+  const int nb = (T + kLossSlotsPerBlock - 1) / kLossSlotsPerBlock;
+  hipLaunchKernelGGL(ce_kernel, dim3(nb, R), dim3(256), 0, s, lp, len, R, T, g, ws);
+  hipLaunchKernelGGL(ce_final_kernel, dim3(1), dim3(256), 0, s, ws, R * nb, len, R, T, loss);
   return hipGetLastError();
 }
 

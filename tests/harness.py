@@ -83,6 +83,14 @@ class GpuProblem:
                               self.loss_ws)
         return loss, g, gz, resid
 
+    def ce(self, logp):
+        import torch
+        cfg = self.cfg
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        g = torch.full((cfg.N,), 5.0, dtype=torch.float32, device="cuda")
+        self.L.ce_loss(logp, self.lens, cfg.R, cfg.T, loss, g, self.loss_ws)
+        return loss, g
+
     def check(self):
         return self.L.lmhead_check(self.ws)
 

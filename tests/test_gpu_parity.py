@@ -172,3 +172,17 @@ def test_accumulate_dw_flag_and_reproducibility():
     base = torch.full((cfg.V, cfg.d), 0.5, dtype=torch.float32, device="cuda")
     _, dW3 = gp_acc.bwd(lse, g, dW_init=base.clone())
     assert torch.allclose(dW3, dW1 + 0.5, atol=1e-6)
+
+
+def test_cross_entropy_objective_end_to_end():
+    # the paper's L_CE (Eq. 9) through the same kernels: forward -> ce_loss -> backward
+    cfg = wl.CONFIGS[1].scaled(P=2, G=3, T=80, d=192, V=6000 + 37)
+    inp = small_inputs(cfg)
+    gp, (logp, lse, ent), (o_lp, o_lse, o_ent) = _fwd_parity(cfg, inp)
+    loss, g = gp.ce(logp)
+    o_loss, o_g = O.ce_loss(o_lp, inp["lens"], cfg.T)
+    assert abs(float(loss.item()) - o_loss) <= TOL_LOSS * abs(o_loss)
+    assert rel_fro(np64(g), o_g) <= 1e-6
+    dH, dW = gp.bwd(lse, g)
+    o_dH, o_dW = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, o_g)
+    assert rel_fro(np64(dH), o_dH) <= TOL_GRAD and rel_fro(np64(dW), o_dW) <= TOL_GRAD

@@ -90,6 +90,10 @@ def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert f(p, None, p, p, p, 2, 4, 32, 1.0, p, p, None, None, p, lws, None) == -1
     assert f(p, p, p, p, p, 2, 4, -32, 1.0, p, p, None, None, p, lws, None) == -2
     assert f(p, p, p, p, p, 2, 4, 32, 1.0, p, p, None, None, p, 8, None) == -5
+    c = lib.ce_loss
+    assert c(p, None, 8, 32, p, p, p, lws, None) == -1
+    assert c(p, p, 0, 32, p, p, p, lws, None) == -2
+    assert c(p, p, 8, 32, p, p, p, 4, None) == -5
     assert lib.lmhead_check(None, None) == -1
     ms, n = C.c_double(), C.c_int64()
     assert lib.lmhead_timing_read(9, C.byref(ms), C.byref(n)) == -2
