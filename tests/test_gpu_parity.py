@@ -186,3 +186,44 @@ def test_cross_entropy_objective_end_to_end():
     dH, dW = gp.bwd(lse, g)
     o_dH, o_dW = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, o_g)
     assert rel_fro(np64(dH), o_dH) <= TOL_GRAD and rel_fro(np64(dW), o_dW) <= TOL_GRAD
+
+
+def test_objective_variants_asymmetric_clip_token_mean_per_response_logz():
+    """The objective variants next to the two headline losses, each against the oracle on the same fp32
+    log-probabilities: clip_lo != clip_hi with the global token mean, FlowRL with one logZ per response
+    (a P' = R, G' = 1 call) and FlowRL on group-normalised rewards."""
+    cfg = wl.CONFIGS[1].scaled(P=6, G=8, T=300, d=64, V=512)
+    lens = wl.lengths(cfg)
+    lp, lo, lr = wl.synthetic_logprobs(cfg)
+    mask = O.index_build(lens, cfg.T)[0]
+    dummy = np.zeros((8, cfg.d), dtype=np.uint16)
+    gp = GpuProblem(cfg, dummy, dummy, np.zeros(cfg.N, dtype=np.int32), lens)
+    d_lp, d_lo, d_lr = (to_device(a) for a in (lp, lo, lr))
+    adv = gp.advantage(wl.rewards(cfg), ddof=1)
+    o_adv = O.group_advantage(wl.rewards(cfg), cfg.P, cfg.G, 1e-6, 1)
+    assert np.abs(np64(adv) - o_adv).max() <= 1e-4
+    for clip_lo, clip_hi, kl, agg in ((0.2, 0.28, 0.04, 1), (0.1, 0.4, 0.0, 0), (0.3, 0.2, 0.1, 1)):
+        loss, g, stats = gp.grpo(d_lp, d_lo, d_lr, adv, clip_lo, clip_hi, kl, agg)
+        args = (np64(d_lp), np64(d_lo), np64(d_lr), o_adv, lens, cfg.P, cfg.G, cfg.T, clip_lo, clip_hi, kl, agg)
+        o_loss, o_g, o_stats = O.grpo_loss(*args)
+        scale = max(abs(o_loss), O.grpo_abs_scale(*args))
+        assert abs(float(loss.item()) - o_loss) <= TOL_LOSS * scale
+        assert np.all(np64(g)[mask == 0] == 0) and rel_fro(np64(g), o_g) <= 1e-3
+
+    # one logZ per response: the same entry point with P' = R, G' = 1
+    per = cfg.scaled(P=cfg.R, G=1)
+    gpr = GpuProblem(per, dummy, dummy, np.zeros(cfg.N, dtype=np.int32), lens)
+    rng = np.random.default_rng(5)
+    logz_r = rng.standard_normal(cfg.R).astype(np.float32)
+    rewards = rng.random(cfg.R).astype(np.float32)
+    loss, g, gz, resid = gpr.flowrl(d_lp, d_lr, rewards, logz_r, 15.0)
+    o = O.flowrl_tb_loss(np64(d_lp), np64(d_lr), rewards, logz_r, lens, cfg.R, 1, cfg.T, 15.0)
+    assert abs(float(loss.item()) - o[0]) <= TOL_LOSS * abs(o[0])
+    assert rel_fro(np64(g), o[1]) <= 1e-3 and rel_fro(np64(gz), o[2]) <= 1e-3
+    assert np.abs(np64(resid) - o[3]).max() <= 1e-3 * np.abs(o[3]).max()
+
+    # rewards normalised by the caller (here: the group-relative advantages) are used as passed
+    loss, g, gz, resid = gp.flowrl(d_lp, d_lr, np64(adv).astype(np.float32), wl.log_z(cfg), 1.0)
+    o = O.flowrl_tb_loss(np64(d_lp), np64(d_lr), np64(adv), wl.log_z(cfg), lens, cfg.P, cfg.G, cfg.T, 1.0)
+    assert abs(float(loss.item()) - o[0]) <= TOL_LOSS * abs(o[0])
+    assert rel_fro(np64(g), o[1]) <= 1e-3 and rel_fro(np64(gz), o[2]) <= 1e-3
