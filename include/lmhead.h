@@ -195,11 +195,12 @@ LMHEAD_API int lmhead_check(void* ws, void* stream);
 
 /*
  * Optional instrumentation for benchmarks (the only process-wide state of the library; not
- * thread-safe).  lmhead_timing_enable(1) makes lmhead_logprob_fwd/bwd bracket each of their
- * matrix-core kernel launches with two HIP events on the launch stream (a fixed pool of 8192
+ * thread-safe).  lmhead_timing_enable(1) makes lmhead_logprob_fwd/bwd and the dynakv_* calls
+ * (dynakv.h) bracket each of their main kernel launches with two HIP events on the launch stream (a fixed pool of 8192
  * pairs; launches beyond it are not timed) and clears earlier records; (0) turns it off.
  * lmhead_timing_read waits for the recorded events and returns, for one kernel kind
- * (0 = logits forward, 1 = dZ recompute, 2 = dH contraction, 3 = dW contraction), the summed
+ * (0 = logits forward, 1 = dZ recompute, 2 = dH contraction, 3 = dW contraction, 4 = spectral
+ * projection, 5 = gate logits, 6 = truncation mask, 7 = low-rank reconstruction), the summed
  * elapsed milliseconds and the number of launches since the last enable call.
  */
 LMHEAD_API int lmhead_timing_enable(int on);

@@ -1,6 +1,7 @@
 """MI355X-native fused LM-head log-probability objective (HIP, gfx950).
 
-Thin Python binding over the C ABI declared in ``include/lmhead.h``.  PyTorch is
+Thin Python binding over the C ABI declared in ``include/lmhead.h`` and, for the
+token-adaptive KV-cache compression path, ``include/dynakv.h``.  PyTorch is
 used only to own device memory and streams; every step of the path runs in the
 library's HIP kernels.  There is no CPU fallback: if the shared library is
 missing or no GPU is present, the compute entry points raise.
@@ -26,7 +27,22 @@ from .binding import (
     EXPORTED_SYMBOLS,
 )
 
+from .dynakv import (
+    DynakvDesc,
+    make_kv_desc,
+    dynakv_workspace_bytes,
+    dynakv_validate_desc,
+    dynakv_gate,
+    dynakv_store,
+    dynakv_reconstruct,
+    dynakv_retain,
+    dynakv_check,
+    DYNAKV_SYMBOLS,
+)
+
 __all__ = [
+    "DynakvDesc", "make_kv_desc", "dynakv_workspace_bytes", "dynakv_validate_desc", "dynakv_gate",
+    "dynakv_store", "dynakv_reconstruct", "dynakv_retain", "dynakv_check", "DYNAKV_SYMBOLS",
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",

@@ -200,4 +200,40 @@ hipError_t launch_flowrl(const float* lp, const float* lr, const float* reward, 
 
 constexpr int kLossSlotsPerBlock = 2048;
 
+// ---- optional per-kernel timing -------------------------------------------------------
+// When enabled, each MFMA kernel launch is bracketed by two HIP events recorded on the launch
+// stream.  The pool is fixed-size; launches beyond it are simply not timed.
+// Kinds: 0 logits fwd, 1 dZ recompute, 2 dH, 3 dW, 4 spectral projection, 5 gate logits,
+// 6 truncation mask, 7 low-rank reconstruction.
+constexpr int kTimingKinds = 8;
+constexpr int kTimingPool = 8192;
+struct TimingState {
+  bool on = false;
+  int used = 0;
+  hipEvent_t start[kTimingPool];
+  hipEvent_t stop[kTimingPool];
+  int kind[kTimingPool];
+  int created = 0;
+};
+extern TimingState g_timing;
+
+struct TimedLaunch {
+  hipStream_t s;
+  int slot = -1;
+  TimedLaunch(int kind, hipStream_t stream) : s(stream) {
+    if (!g_timing.on || g_timing.used >= g_timing.created) return;
+    slot = g_timing.used++;
+    g_timing.kind[slot] = kind;
+    (void)hipEventRecord(g_timing.start[slot], s);
+  }
+  ~TimedLaunch() {
+    if (slot >= 0) (void)hipEventRecord(g_timing.stop[slot], s);
+  }
+};
+
+#define LM_TRY(expr)                               \
+  do {                                             \
+    if ((expr) != hipSuccess) return LMHEAD_E_HIP; \
+  } while (0)
+
 }  // namespace lmhead

@@ -1,0 +1,448 @@
+// Bandwidth-bound kernels of the KV-compression path: the truncation mask (softmax, cumulative
+// sum, threshold; Eqs. 5-8), the ragged store (offset scan + segment copy), the grouping of
+// tokens by contraction length for the reconstruction, and the retain rate (Eqs. 4 and 9).
+// Rows are handled one wavefront per token with 16-byte accesses.
+#include "dynakv_common.h"
+
+namespace lmhead {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+template <typename T>
+struct Store4;
+template <>
+struct Store4<float> {
+  __device__ static inline void load(const float* p, float (&v)[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  __device__ static inline void store(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <>
+struct Store4<__bf16> {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+  __device__ static inline void load(const __bf16* p, float (&v)[4]) {
+    const bf16x4_t t = *reinterpret_cast<const bf16x4_t*>(p);
+    v[0] = (float)t.x; v[1] = (float)t.y; v[2] = (float)t.z; v[3] = (float)t.w;
+  }
+  __device__ static inline void store(__bf16* p, const float (&v)[4]) {
+    const bf16x4_t t = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+    *reinterpret_cast<bf16x4_t*>(p) = t;
+  }
+};
+
+// ---- truncation mask -----------------------------------------------------------------------
+//
+// One wavefront per token.  Mask position i belongs to gate column j(i) = i (reverse cumulative
+// sum) or j(i) = d-1-i (Eq. 6 as printed: Flip(cumsum(p))_i = sum_{i' >= i} p_{d-1-i'}), so both
+// readings are the same suffix sum over positions.  Positions are walked in groups of 256 (four
+// per lane, contiguous), last group first, carrying the running suffix.  The row of logits
+// (4 KB at d = 1024) is read three times (max, sum, suffix); the second and third read hit L1/L2.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ logits,
+                                                      const float* __restrict__ bias,
+                                                      const T* __restrict__ xt, int64_t n, int d, float tau,
+                                                      int literal, int32_t* __restrict__ k_out,
+                                                      float* __restrict__ m_out, T* __restrict__ xhat) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tok = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tok >= n) return;
+  const float* z = logits + tok * d;
+  const int ngroups = (d + 255) / 256;
+
+  // logits (+ bias) of the four positions that start at i0, in position order
+  auto load4 = [&](int i0, float (&v)[4]) {
+    if (!literal) {
+      const float4 a = *reinterpret_cast<const float4*>(z + i0);
+      const float4 b = *reinterpret_cast<const float4*>(bias + i0);
+      v[0] = a.x + b.x; v[1] = a.y + b.y; v[2] = a.z + b.z; v[3] = a.w + b.w;
+    } else {
+      const int j0 = d - 4 - i0;   // columns j0 .. j0+3 are positions i0+3 .. i0
+      const float4 a = *reinterpret_cast<const float4*>(z + j0);
+      const float4 b = *reinterpret_cast<const float4*>(bias + j0);
+      v[0] = a.w + b.w; v[1] = a.z + b.z; v[2] = a.y + b.y; v[3] = a.x + b.x;
+    }
+  };
+
+  float mx = -__builtin_huge_valf();
+  for (int g = 0; g < ngroups; ++g) {
+    const int i0 = g * 256 + lane * 4;
+    if (i0 < d) {
+      float v[4];
+      load4(i0, v);
+      mx = fmaxf(fmaxf(mx, fmaxf(v[0], v[1])), fmaxf(v[2], v[3]));
+    }
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int g = 0; g < ngroups; ++g) {
+    const int i0 = g * 256 + lane * 4;
+    if (i0 < d) {
+      float v[4];
+      load4(i0, v);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+    }
+  }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+
+  float carry = 0.f;   // sum of exp over all positions after the current group
+  int count = 0;
+  for (int g = ngroups - 1; g >= 0; --g) {
+    const int i0 = g * 256 + lane * 4;
+    const bool on = i0 < d;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (on) {
+      float v[4];
+      load4(i0, v);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] = __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+      s[2] += s[3];
+      s[1] += s[2];
+      s[0] += s[1];
+    }
+    // inclusive suffix sum of the lanes' totals (lanes above this one)
+    float incl = s[0];
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const float y = __shfl_down(incl, o);
+      if (lane + o < 64) incl += y;
+    }
+    const float above = carry + (incl - s[0]);
+    carry += __shfl(incl, 0);
+    if (on) {
+      float mk[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        mk[e] = (above + s[e]) * inv;
+        count += mk[e] > tau ? 1 : 0;
+      }
+      if (m_out) Store4<float>::store(m_out + tok * d + i0, mk);
+      if (xhat) {
+        float xv[4];
+        Store4<T>::load(xt + tok * d + i0, xv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) xv[e] *= mk[e];
+        Store4<T>::store(xhat + tok * d + i0, xv);
+      }
+    }
+  }
+  count = wave_sum_i(count);
+  if (lane == 0) k_out[tok] = count;
+}
+
+// ---- ragged store ---------------------------------------------------------------------------
+
+__device__ inline int seg_len(int k, int d, int& bad) {
+  if (k < 0 || k > d) {
+    bad = 1;
+    k = k < 0 ? 0 : d;
+  }
+  return (k + DYNAKV_GRANULE - 1) / DYNAKV_GRANULE * DYNAKV_GRANULE;
+}
+
+// Block totals of the segment lengths (kKvScanBlock tokens per block).
+__global__ __launch_bounds__(256) void kv_scan_totals_kernel(const int32_t* __restrict__ k, int64_t n, int d,
+                                                             int64_t* __restrict__ blocksum, WsHeader* hdr) {
+  __shared__ int wsum[4];
+  const int64_t base = (int64_t)blockIdx.x * kKvScanBlock;
+  int bad = 0, tot = 0;
+  for (int i = threadIdx.x; i < kKvScanBlock; i += 256)
+    if (base + i < n) tot += seg_len(k[base + i], d, bad);
+  tot = wave_sum_i(tot);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = tot;
+  if (bad) atomicOr(&hdr->err, kErrKvCount);
+  __syncthreads();
+  if (threadIdx.x == 0) blocksum[blockIdx.x] = (int64_t)wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// One workgroup: blocksum <- its exclusive prefix sum; blocksum[nblocks] = grand total.
+__global__ __launch_bounds__(1024) void kv_scan_blocks_kernel(int64_t* __restrict__ blocksum, int nblocks) {
+  __shared__ int64_t buf[1024];
+  __shared__ int64_t carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int base = 0; base < nblocks; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int64_t x = i < nblocks ? blocksum[i] : 0;
+    buf[threadIdx.x] = x;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int64_t y = threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
+      __syncthreads();
+      buf[threadIdx.x] += y;
+      __syncthreads();
+    }
+    const int64_t carry = carry_s;
+    if (i < nblocks) blocksum[i] = carry + buf[threadIdx.x] - x;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry_s = carry + buf[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) blocksum[nblocks] = carry_s;
+}
+
+// off[i] = prefix of the block + exclusive prefix inside the block; off[n] = grand total.
+__global__ __launch_bounds__(1024) void kv_scan_offsets_kernel(const int32_t* __restrict__ k, int64_t n, int d,
+                                                               const int64_t* __restrict__ blocksum,
+                                                               int nblocks, int64_t* __restrict__ off) {
+  __shared__ int buf[1024];
+  const int64_t i = (int64_t)blockIdx.x * kKvScanBlock + threadIdx.x;
+  int bad = 0;
+  const int x = i < n ? seg_len(k[i], d, bad) : 0;
+  buf[threadIdx.x] = x;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int y = threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
+    __syncthreads();
+    buf[threadIdx.x] += y;
+    __syncthreads();
+  }
+  if (i < n) off[i] = blocksum[blockIdx.x] + buf[threadIdx.x] - x;
+  if (i == n - 1) off[n] = blocksum[nblocks];
+}
+static_assert(kKvScanBlock == 1024, "the offset kernel scans one token per thread");
+
+// One wavefront per token: copy the segment, zero the tail of its last granule.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_pack_kernel(const T* __restrict__ xt, const int32_t* __restrict__ k,
+                                                      const int64_t* __restrict__ off, int64_t n, int d,
+                                                      T* __restrict__ packed, int64_t capacity, WsHeader* hdr) {
+  constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
+  const int lane = threadIdx.x & 63;
+  const int64_t tok = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tok >= n) return;
+  int bad = 0;
+  const int kk = min(max(k[tok], 0), d);
+  const int seg = seg_len(kk, d, bad);
+  const int64_t o = off[tok];
+  if (o + seg > capacity) {
+    if (lane == 0) atomicOr(&hdr->err, kErrKvCapacity);
+    return;
+  }
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  for (int c = lane; c * EPC < seg; c += 64) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(xt + tok * d + c * EPC);
+    if ((c + 1) * EPC > kk) {
+      T e[EPC];
+      __builtin_memcpy(e, &v, 16);
+#pragma unroll
+      for (int j = 0; j < EPC; ++j)
+        if (c * EPC + j >= kk) e[j] = (T)0.0f;
+      __builtin_memcpy(&v, e, 16);
+    }
+    *reinterpret_cast<u32x4*>(packed + o + c * EPC) = v;
+  }
+}
+
+// ---- grouping by contraction length --------------------------------------------------------
+
+__global__ __launch_bounds__(256) void kv_fill_i32_kernel(int32_t* __restrict__ p, int64_t count, int32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) p[i] = v;
+}
+
+__device__ inline int bucket_of(int k, int d, int esz) {
+  k = min(max(k, 0), d);
+  return (k * esz + 127) / 128;
+}
+
+__global__ __launch_bounds__(256) void kv_hist_kernel(const int32_t* __restrict__ k, int64_t n, int d, int esz,
+                                                      int nbuckets, int32_t* __restrict__ hist) {
+  extern __shared__ int32_t h[];
+  for (int i = threadIdx.x; i < nbuckets; i += 256) h[i] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * 4096;
+  for (int i = threadIdx.x; i < 4096; i += 256)
+    if (base + i < n) atomicAdd(&h[bucket_of(k[base + i], d, esz)], 1);
+  __syncthreads();
+  for (int i = threadIdx.x; i < nbuckets; i += 256)
+    if (h[i]) atomicAdd(&hist[i], h[i]);
+}
+
+// start[b] = number of tokens in longer buckets (descending order of step count)
+__global__ void kv_bucket_start_kernel(int32_t* __restrict__ hist, int nbuckets) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int32_t run = 0;
+  for (int b = nbuckets - 1; b >= 0; --b) {
+    hist[nbuckets + b] = run;
+    run += hist[b];
+  }
+}
+
+// The position inside a bucket comes from an integer atomic, so `order` may differ from run to run
+// within a bucket; the reconstruction's results do not depend on it (a token's output only
+// involves its own row, and extra K-steps of a tile add exact zeros).
+__global__ __launch_bounds__(256) void kv_scatter_kernel(const int32_t* __restrict__ k, int64_t n, int d, int esz,
+                                                         int nbuckets, int32_t* __restrict__ hist,
+                                                         int32_t* __restrict__ order) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int b = bucket_of(k[i], d, esz);
+  const int pos = atomicAdd(&hist[2 * nbuckets + b], 1);
+  order[hist[nbuckets + b] + pos] = (int32_t)i;
+}
+
+// ---- retain rate ----------------------------------------------------------------------------
+
+// red[2*b] = sum of k over the block's 256 tokens, red[2*b+1] = sum of m over their rows.
+__global__ __launch_bounds__(256) void kv_retain_partial_kernel(const int32_t* __restrict__ k,
+                                                                const float* __restrict__ m, int64_t n, int d,
+                                                                double* __restrict__ red) {
+  __shared__ double sk[4], sm[4];
+  const int64_t t0 = (int64_t)blockIdx.x * 256;
+  const int64_t tn = min((int64_t)256, n - t0);
+  int ks = 0;
+  if (k && threadIdx.x < tn) ks = min(max(k[t0 + threadIdx.x], 0), d);
+  float ms = 0.f;
+  if (m) {
+    const int64_t cnt4 = tn * d / 4;
+    const float4* p = reinterpret_cast<const float4*>(m + t0 * d);
+    for (int64_t i = threadIdx.x; i < cnt4; i += 256) {
+      const float4 v = p[i];
+      ms += (v.x + v.y) + (v.z + v.w);
+    }
+  }
+  ks = wave_sum_i(ks);
+  ms = wave_sum(ms);
+  if ((threadIdx.x & 63) == 0) {
+    sk[threadIdx.x >> 6] = ks;
+    sm[threadIdx.x >> 6] = ms;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    red[2 * blockIdx.x] = (sk[0] + sk[1]) + (sk[2] + sk[3]);
+    red[2 * blockIdx.x + 1] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+  }
+}
+
+__global__ __launch_bounds__(256) void kv_retain_final_kernel(const double* __restrict__ red, int nblocks,
+                                                              int64_t n, int d, float alpha, int have_k,
+                                                              int have_m, float* __restrict__ out) {
+  __shared__ double sk[256], sm[256];
+  double a = 0.0, b = 0.0;
+  for (int i = threadIdx.x; i < nblocks; i += 256) {
+    a += red[2 * i];
+    b += red[2 * i + 1];
+  }
+  sk[threadIdx.x] = a;
+  sm[threadIdx.x] = b;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) {
+      sk[threadIdx.x] += sk[threadIdx.x + o];
+      sm[threadIdx.x] += sm[threadIdx.x + o];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double nd = (double)n * d;
+    const double rh = have_k ? sk[0] / nd : 0.0;
+    const double rs = have_m ? sm[0] / nd : 0.0;
+    out[0] = (float)rh;
+    out[1] = (float)rs;
+    out[2] = (float)(alpha * rs * rs);
+  }
+}
+
+__global__ __launch_bounds__(256) void kv_retain_grad_kernel(const float* __restrict__ out, float alpha,
+                                                             int64_t count4, double nd, float* __restrict__ g) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count4) return;
+  const float v = (float)(2.0 * alpha * (double)out[1] / nd);
+  reinterpret_cast<float4*>(g)[i] = make_float4(v, v, v, v);
+}
+
+__global__ void kv_clear_header_kernel(WsHeader* hdr) {
+  if (threadIdx.x == 0) {
+    hdr->err = 0;
+    hdr->nv = 0;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_kv_clear_header(WsHeader* hdr, hipStream_t s) {
+  hipLaunchKernelGGL(kv_clear_header_kernel, dim3(1), dim3(64), 0, s, hdr);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const void* xt, int64_t n, int d,
+                          float tau, bool literal, int32_t* k, float* m, void* xhat, hipStream_t s) {
+  const dim3 grid((unsigned)((n + 3) / 4));
+  if (dtype == LMHEAD_BF16)
+    hipLaunchKernelGGL(kv_mask_kernel<__bf16>, grid, dim3(256), 0, s, logits, b, static_cast<const __bf16*>(xt), n,
+                       d, tau, literal ? 1 : 0, k, m, static_cast<__bf16*>(xhat));
+  else
+    hipLaunchKernelGGL(kv_mask_kernel<float>, grid, dim3(256), 0, s, logits, b, static_cast<const float*>(xt), n, d,
+                       tau, literal ? 1 : 0, k, m, static_cast<float*>(xhat));
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t* off,
+                           void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr, hipStream_t s) {
+  const int nblocks = (int)((n + kKvScanBlock - 1) / kKvScanBlock);
+  hipLaunchKernelGGL(kv_scan_totals_kernel, dim3(nblocks), dim3(256), 0, s, k, n, d, blocksum, hdr);
+  hipLaunchKernelGGL(kv_scan_blocks_kernel, dim3(1), dim3(1024), 0, s, blocksum, nblocks);
+  hipLaunchKernelGGL(kv_scan_offsets_kernel, dim3(nblocks), dim3(1024), 0, s, k, n, d, blocksum, nblocks, off);
+  const dim3 grid((unsigned)((n + 3) / 4));
+  if (dtype == LMHEAD_BF16)
+    hipLaunchKernelGGL(kv_pack_kernel<__bf16>, grid, dim3(256), 0, s, static_cast<const __bf16*>(xt), k, off, n, d,
+                       static_cast<__bf16*>(packed), capacity, hdr);
+  else
+    hipLaunchKernelGGL(kv_pack_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(xt), k, off, n, d,
+                       static_cast<float*>(packed), capacity, hdr);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_order(int dtype, const int32_t* k, int64_t n, int64_t ncap, int d, int nbuckets,
+                           int32_t* hist, int32_t* order, WsHeader* hdr, hipStream_t s) {
+  (void)hdr;
+  const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
+  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3((unsigned)((3 * nbuckets + 255) / 256)), dim3(256), 0, s, hist,
+                     (int64_t)3 * nbuckets, 0);
+  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3((unsigned)((ncap + 255) / 256)), dim3(256), 0, s, order, ncap, -1);
+  hipLaunchKernelGGL(kv_hist_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256), nbuckets * sizeof(int32_t), s,
+                     k, n, d, esz, nbuckets, hist);
+  hipLaunchKernelGGL(kv_bucket_start_kernel, dim3(1), dim3(64), 0, s, hist, nbuckets);
+  hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, k, n, d, esz, nbuckets,
+                     hist, order);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_retain(const int32_t* k, const float* m, int64_t n, int d, float alpha, float* out,
+                            float* g_m, double* red, hipStream_t s) {
+  const int nblocks = (int)((n + 255) / 256);
+  hipLaunchKernelGGL(kv_retain_partial_kernel, dim3(nblocks), dim3(256), 0, s, k, m, n, d, red);
+  hipLaunchKernelGGL(kv_retain_final_kernel, dim3(1), dim3(256), 0, s, red, nblocks, n, d, alpha, k ? 1 : 0,
+                     m ? 1 : 0, out);
+  if (g_m) {
+    const int64_t count4 = n * d / 4;
+    hipLaunchKernelGGL(kv_retain_grad_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s, out, alpha,
+                       count4, (double)n * d, g_m);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lmhead

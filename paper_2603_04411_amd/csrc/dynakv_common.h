@@ -1,0 +1,99 @@
+// Internal declarations of the KV-compression path: workspace layout and launcher prototypes.
+#pragma once
+
+#include "../../include/dynakv.h"
+#include "common.h"
+
+namespace lmhead {
+
+constexpr int kKvMaxD = 8192;
+constexpr int kKvScanBlock = 1024;   // tokens per block of the offset scan
+
+// Sticky error bits of this path (same header word as the LM-head path).
+constexpr int kErrKvCount = 4;       // a k outside [0, d]
+constexpr int kErrKvCapacity = 8;    // a segment beyond the capacity of the store
+
+struct KvLayout {
+  int esz;
+  int64_t n, d;
+  int64_t ncap;      // n rounded up to the tile
+  int64_t dp;        // d rounded up to the tile
+  int64_t ldT;       // pitch (elements) of the transposed parameter copies: d + one 128-byte line
+  int nbuckets;      // K-steps a token can need, plus one: d * esz / 128 + 1
+  size_t hdr, UT, WT, UiT, logits, order, hist, blocksum, red, total;
+};
+
+static inline KvLayout make_kv_layout(const dynakv_desc* d) {
+  KvLayout L{};
+  L.esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
+  L.n = d->n;
+  L.d = d->d;
+  L.ncap = (int64_t)round_up((size_t)L.n, kTile);
+  L.dp = (int64_t)round_up((size_t)L.d, kTile);
+  L.ldT = L.d + 128 / L.esz;
+  L.nbuckets = (int)(L.d * L.esz / 128) + 1;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return o;
+  };
+  L.hdr = take(sizeof(WsHeader));
+  L.UT = take((size_t)L.dp * L.ldT * L.esz);
+  L.WT = take((size_t)L.dp * L.ldT * L.esz);
+  L.UiT = take((size_t)L.dp * L.ldT * L.esz);
+  L.logits = take((size_t)L.ncap * L.d * 4);
+  L.order = take((size_t)L.ncap * 4);
+  L.hist = take((size_t)L.nbuckets * 3 * 4);          // counts, start positions, cursors
+  L.blocksum = take((size_t)(L.ncap / kKvScanBlock + 2) * 8);
+  L.red = take((size_t)(L.ncap / 256 + 2) * 2 * 8);   // per-block partial sums of the retain rate
+  L.total = off;
+  return L;
+}
+
+// Plain contraction on the MFMA tile core with a transposed store:
+//   out[row(n)][m] = sum_k A[m][k] * Bop[n][k],  m < M, n < Nn.
+// mode 0/1: Bop rows are dense rows of B (pitch ldB), row(n) = n.  The output is the storage type
+//           (out_e) or fp32 (out_f), whichever is non-null.
+// mode 2:   ragged rows: Bop[n] = packed[off[t] .. off[t] + k[t]) with t = order[n] (order < 0: no
+//           token), zero beyond; row(n) = t; the tile's step count follows its first token.
+struct KvGemmArgs {
+  int mode;
+  const void* A;        // [dp x K] transposed parameter copy, pitch ldA
+  int64_t ldA;
+  const void* B;        // dense rows (mode 0/1) or the packed store (mode 2)
+  int64_t ldB;
+  int64_t bytesB;       // mode 2: bytes readable at B
+  int M;                // output columns (d)
+  int64_t Nn;           // tokens
+  int K;                // contraction length in elements (d)
+  const int32_t* order; // mode 2
+  const int64_t* off;   // mode 2
+  const int32_t* kcnt;  // mode 2
+  void* out_e;
+  float* out_f;
+  int64_t ldo;
+  WsHeader* hdr;
+};
+hipError_t launch_kv_gemm(int dtype, const KvGemmArgs& a, hipStream_t s);
+
+// Softmax over the gate logits (+ bias), the cumulative mask, the threshold count and the
+// optional training outputs.
+hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const void* xt, int64_t n, int d,
+                          float tau, bool literal, int32_t* k, float* m, void* xhat, hipStream_t s);
+
+// off = exclusive prefix sum of roundup(k, 8); then the segments are copied.
+hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t* off,
+                           void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr, hipStream_t s);
+
+// order = tokens sorted by descending number of K-steps (ceil(k * esz / 128)), padded with -1 up to
+// ncap.  hist holds 3 * nbuckets ints of scratch.
+hipError_t launch_kv_order(int dtype, const int32_t* k, int64_t n, int64_t ncap, int d, int nbuckets,
+                           int32_t* hist, int32_t* order, WsHeader* hdr, hipStream_t s);
+
+hipError_t launch_kv_retain(const int32_t* k, const float* m, int64_t n, int d, float alpha, float* out,
+                            float* g_m, double* red, hipStream_t s);
+
+hipError_t launch_kv_clear_header(WsHeader* hdr, hipStream_t s);
+
+}  // namespace lmhead

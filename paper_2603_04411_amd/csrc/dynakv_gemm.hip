@@ -1,0 +1,171 @@
+// Matrix-core kernels of the KV-compression path, built on GemmTile (gemm_core.h):
+//   mode 0  spectral projection     x~ = x U                      (Eq. 1)
+//   mode 1  gate logits             x~ W          (fp32, bias added by the mask kernel; Eq. 5)
+//   mode 2  dynamic low-rank reconstruction  x_bar = x^[0:k] U^-1[0:k, :]   (Eq. 3)
+// All three are  out[row(n)][m] = sum_k A[m][k] Bop[n][k]  with the parameter matrix (transposed
+// copy, K-contiguous) on the MFMA M axis and tokens on N, as in the LM-head kernels.  The
+// parameter matrix (2 MB at d = 1024) stays in every XCD's L2; the token rows stream through once
+// per XCD because an XCD runs all M tiles of a token tile together (tile_map.h).
+//
+// Mode 2 reads token rows of differing length straight from the packed store: row n of a tile is
+// the segment of token order[n], loads beyond the segment's end fetch zeros (GemmTile's kMaskB),
+// and the tile runs as many K-steps as its first token needs: `order` lists tokens by descending
+// step count, so that is the tile's maximum and tiles of short tokens are short.
+#include "dynakv_common.h"
+#include "gemm_core.h"
+
+namespace lmhead {
+
+namespace {
+
+constexpr int kKvMapBx = 4, kKvMapBy = 4;
+
+template <typename E, bool kMask>
+using KvTile = GemmTile<E, 256, 256, 2, 2, /*kLeadB=*/true, kMask>;
+
+template <typename E, int Mode>
+__global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
+  using G = KvTile<E, Mode == 2>;
+  constexpr int ESZ = Elem<E>::size;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int mtiles = (a.M + G::BM - 1) / G::BM;
+  const int ntiles = (int)((a.Nn + G::BN - 1) / G::BN);
+  int mt, nt;
+  if (!xcd_tile_coords(blockIdx.x, mtiles, ntiles, kKvMapBx, kKvMapBy, mt, nt)) return;
+  const int64_t n0 = (int64_t)nt * G::BN;
+  const int m0 = mt * G::BM;
+  const int64_t pitchA = a.ldA * ESZ;
+
+  uint32_t offA[G::A_LD], offB[G::B_LD];
+  int limB[G::B_LD];
+#pragma unroll
+  for (int q = 0; q < G::A_LD; ++q) {
+    const int row = G::ldA_row(q);
+    offA[q] = (uint32_t)(row * pitchA) + G::ld_byte(row);
+  }
+  const char* Bbase;
+  uint32_t bytesB;
+  int ksteps;
+  if constexpr (Mode == 2) {
+    int bad = 0;
+#pragma unroll
+    for (int q = 0; q < G::B_LD; ++q) {
+      const int row = G::ldB_row(q);
+      const int t = a.order[n0 + row];
+      offB[q] = 0x80000000u;
+      limB[q] = 0;
+      if (t >= 0) {
+        const int64_t o = a.off[t];
+        const int kk = min(max(a.kcnt[t], 0), a.M);
+        const int seg = (kk + DYNAKV_GRANULE - 1) / DYNAKV_GRANULE * DYNAKV_GRANULE;
+        if (o < 0 || (o & (DYNAKV_GRANULE - 1)) || (o + seg) * ESZ > a.bytesB) {
+          bad = 1;
+        } else {
+          offB[q] = (uint32_t)(o * ESZ) + G::ld_byte(row);
+          limB[q] = seg * ESZ - G::ld_byte(row);
+        }
+      }
+    }
+    if (bad) atomicOr(&a.hdr->err, kErrKvCapacity);
+    const int t0 = a.order[n0];
+    const int k0 = t0 < 0 ? 0 : min(max(a.kcnt[t0], 0), a.M);
+    ksteps = (k0 * ESZ + G::KB - 1) / G::KB;
+    Bbase = static_cast<const char*>(a.B);
+    bytesB = (uint32_t)a.bytesB;
+  } else {
+    const int64_t pitchB = a.ldB * ESZ;
+    const int last = (int)min((int64_t)G::BN - 1, a.Nn - 1 - n0);   // rows past the end re-read the last one
+#pragma unroll
+    for (int q = 0; q < G::B_LD; ++q) {
+      const int row = G::ldB_row(q);
+      offB[q] = (uint32_t)(min(row, last) * pitchB) + G::ld_byte(row);
+      limB[q] = 0;
+    }
+    ksteps = a.K * ESZ / G::KB;
+    Bbase = static_cast<const char*>(a.B) + n0 * pitchB;
+    bytesB = 0x7fffffffu;
+  }
+
+  typename G::Acc acc;
+  G::zero(acc);
+  G::run_rows(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA, Bbase, offB, limB, bytesB, ksteps,
+              smem);
+
+  // The tile leaves through LDS as [n][m] rows of fp32 so that each output row segment is
+  // written by one wavefront instruction (16 bytes per lane for fp32, 8 for bf16).
+  constexpr int JG = 2;
+  constexpr int NCOL = G::WGN * JG * 32;
+  constexpr int P = G::BM * 4 + 16;
+  static_assert(NCOL * P <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
+  static_assert(G::BM * 4 / 16 == 64, "one staged row is one wavefront store");
+#pragma unroll
+  for (int jg = 0; jg < G::TN / JG; ++jg) {
+#pragma unroll
+    for (int jj = 0; jj < JG; ++jj) {
+      const int j = jg * JG + jj;
+      const int nl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);
+#pragma unroll
+      for (int i = 0; i < G::TM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
+        }
+    }
+    __syncthreads();
+    const int c = G::lane();
+    const int m = m0 + c * 4;
+#pragma unroll 4
+    for (int r = G::wave(); r < NCOL; r += G::NWAVES) {
+      const int ntl = (r / (JG * 32)) * G::WN + jg * (JG * 32) + r % (JG * 32);   // column within the tile
+      int64_t row = n0 + ntl;
+      if constexpr (Mode == 2) {
+        row = a.order[row];
+      } else {
+        if (row >= a.Nn) row = -1;
+      }
+      if (row < 0 || m >= a.M) continue;
+      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(smem + r * P + c * 16);
+      if (a.out_f) {
+        *reinterpret_cast<f32x4_t*>(a.out_f + row * a.ldo + m) = v;
+      } else if constexpr (ESZ == 4) {
+        *reinterpret_cast<f32x4_t*>(static_cast<float*>(a.out_e) + row * a.ldo + m) = v;
+      } else {
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+        const bf16x4_t h = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+        *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = h;
+      }
+    }
+    if (jg + 1 < G::TN / JG) __syncthreads();
+  }
+}
+
+template <typename E, int Mode>
+hipError_t launch_mode(const KvGemmArgs& a, hipStream_t s) {
+  using G = KvTile<E, Mode == 2>;
+  const int mtiles = (a.M + G::BM - 1) / G::BM;
+  const int64_t ntiles = (a.Nn + G::BN - 1) / G::BN;
+  const dim3 grid(xcd_grid_size(mtiles, ntiles, kKvMapBy));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_gemm_kernel<E, Mode>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((kv_gemm_kernel<E, Mode>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  return hipGetLastError();
+}
+
+template <typename E>
+hipError_t launch_e(const KvGemmArgs& a, hipStream_t s) {
+  switch (a.mode) {
+    case 0: return launch_mode<E, 0>(a, s);
+    case 1: return launch_mode<E, 1>(a, s);
+    default: return launch_mode<E, 2>(a, s);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_kv_gemm(int dtype, const KvGemmArgs& a, hipStream_t s) {
+  return dtype == LMHEAD_BF16 ? launch_e<bf16_tag>(a, s) : launch_e<f32_tag>(a, s);
+}
+
+}  // namespace lmhead

@@ -85,7 +85,8 @@ constexpr int kWaitVm0 = wait_vm(0);
 constexpr int kWaitLgkm0 = 0xC07F;
 
 // kLeadB selects which operand goes first round the LDS ring (see run()).
-template <typename E, int BM_, int BN_, int WGM_, int WGN_, bool kLeadB = false>
+// kMaskB: every B row has its own K extent (ragged rows); loads past it fetch zeros (see run()).
+template <typename E, int BM_, int BN_, int WGM_, int WGN_, bool kLeadB = false, bool kMaskB = false>
 struct GemmTile {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
   static constexpr int NWAVES = WGM * WGN;
@@ -147,6 +148,20 @@ struct GemmTile {
   __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                     const char* __restrict__ B, const uint32_t (&offB)[B_LD],
                                     int ksteps, char* lds) {
+    static_assert(!kMaskB, "ragged rows need their limits");
+    const int none[B_LD] = {};
+    run_rows(acc, A, offA, B, offB, none, 0x7fffffffu, ksteps, lds);
+  }
+
+  // Same, with B given as one buffer of `bytesB` bytes (at most 2^31) that holds rows of differing
+  // K extent: offB[q] is the byte offset of this lane's chunk of its row at K-step 0, and with
+  // kMaskB the load of K-step ks is taken only while ks * KB < limB[q] (limB[q] = the row's extent
+  // in bytes, a multiple of 16, minus the lane's byte position in the step); otherwise the lane
+  // asks for an offset outside the buffer, which the hardware range check turns into zeros in
+  // LDS without touching memory.
+  __device__ static inline void run_rows(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
+                                         const char* __restrict__ B, const uint32_t (&offB)[B_LD],
+                                         const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds) {
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int w = wave();
     const int l = lane();
@@ -169,7 +184,8 @@ struct GemmTile {
       return reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
     };
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(A), 0, 0x7fffffff, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(B), 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(B), 0, (int)__builtin_amdgcn_readfirstlane(bytesB), 0x00020000);
     auto issue_a = [&](int ks, int slot, int part) {
       char* st = lds + slot * SLOT;
 #pragma unroll
@@ -179,8 +195,11 @@ struct GemmTile {
     auto issue_b = [&](int ks, int slot, int part) {
       char* st = lds + slot * SLOT;
 #pragma unroll
-      for (int q = part * (B_LD / NPART); q < (part + 1) * (B_LD / NPART); ++q)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(st + (w * B_LD + q) * 1024), 16, offB[q], ks * KB, 0, 0);
+      for (int q = part * (B_LD / NPART); q < (part + 1) * (B_LD / NPART); ++q) {
+        uint32_t vo = offB[q];
+        if constexpr (kMaskB) vo = (ks * KB < limB[q]) ? vo : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(st + (w * B_LD + q) * 1024), 16, vo, ks * KB, 0, 0);
+      }
     };
 
     u32x4_t fa[2][TM], fb[2][TN];

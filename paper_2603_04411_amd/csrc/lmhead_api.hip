@@ -32,40 +32,6 @@ struct Ws {
   T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
 };
 
-// ---- optional per-kernel timing -------------------------------------------------------
-// When enabled, each MFMA kernel launch is bracketed by two HIP events recorded on the launch
-// stream.  The pool is fixed-size; launches beyond it are simply not timed.
-constexpr int kTimingKinds = 4;  // 0 logits fwd, 1 dZ recompute, 2 dH, 3 dW
-constexpr int kTimingPool = 8192;
-struct TimingState {
-  bool on = false;
-  int used = 0;
-  hipEvent_t start[kTimingPool];
-  hipEvent_t stop[kTimingPool];
-  int kind[kTimingPool];
-  int created = 0;
-};
-TimingState g_timing;
-
-struct TimedLaunch {
-  hipStream_t s;
-  int slot = -1;
-  TimedLaunch(int kind, hipStream_t stream) : s(stream) {
-    if (!g_timing.on || g_timing.used >= g_timing.created) return;
-    slot = g_timing.used++;
-    g_timing.kind[slot] = kind;
-    (void)hipEventRecord(g_timing.start[slot], s);
-  }
-  ~TimedLaunch() {
-    if (slot >= 0) (void)hipEventRecord(g_timing.stop[slot], s);
-  }
-};
-
-#define LM_TRY(expr)                         \
-  do {                                       \
-    if ((expr) != hipSuccess) return LMHEAD_E_HIP; \
-  } while (0)
-
 size_t loss_ws_bytes(int64_t P, int64_t G, int64_t T) {
   const int64_t R = P * G;
   const int64_t nb = (T + kLossSlotsPerBlock - 1) / kLossSlotsPerBlock;
@@ -80,6 +46,10 @@ int validate_pgt(int32_t P, int32_t G, int32_t T) {
 }
 
 }  // namespace
+
+namespace lmhead {
+TimingState g_timing;
+}
 
 extern "C" {
 

@@ -111,3 +111,60 @@ def small_inputs(cfg):
         H=wl.hidden(cfg), W=wl.weight(cfg), W_old=wl.weight(cfg, "old"), W_ref=wl.weight(cfg, "ref"),
         tok=wl.tokens(cfg), lens=wl.lengths(cfg), rewards=wl.rewards(cfg), logZ=wl.log_z(cfg),
     )
+
+
+class KvProblem:
+    """Device tensors and workspace of one KV-compression workload (include/dynakv.h)."""
+
+    def __init__(self, cfg, inp, flags=0, ldx=None):
+        import torch
+        import paper_2603_04411_amd as L
+        self.L, self.cfg = L, cfg
+        self.tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        x = inp["x"]
+        if ldx is not None and ldx != cfg.d:          # rows embedded in a wider buffer
+            wide = np.zeros((cfg.n, ldx), dtype=x.dtype)
+            wide[:, : cfg.d] = x
+            x = wide
+        self.desc = L.make_kv_desc(cfg.n, cfg.d, cfg.dtype, ldx=ldx, flags=flags)
+        assert L.dynakv_validate_desc(self.desc) == 0
+        self.x, self.U, self.W, self.U_inv = (to_device(a) for a in (x, inp["U"], inp["W"], inp["U_inv"]))
+        self.b = to_device(inp["b"])
+        self.ws = torch.empty(L.dynakv_workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
+
+    def gate(self, tau, soft=True):
+        import torch
+        cfg = self.cfg
+        xt = torch.full((cfg.n, cfg.d), 3.0, dtype=self.tdt, device="cuda")
+        k = torch.full((cfg.n,), -7, dtype=torch.int32, device="cuda")
+        m = torch.full((cfg.n, cfg.d), 3.0, dtype=torch.float32, device="cuda") if soft else None
+        xhat = torch.full((cfg.n, cfg.d), 3.0, dtype=self.tdt, device="cuda") if soft else None
+        self.L.dynakv_gate(self.desc, self.x, self.U, self.W, self.b, tau, xt, k, m, xhat, self.ws)
+        return xt, k, m, xhat
+
+    def store(self, xt, k, capacity=None):
+        import torch
+        cfg = self.cfg
+        capacity = cfg.n * cfg.d if capacity is None else capacity
+        off = torch.full((cfg.n + 1,), -1, dtype=torch.int64, device="cuda")
+        packed = torch.full((max(capacity, 8),), 5.0, dtype=self.tdt, device="cuda")
+        self.L.dynakv_store(self.desc, xt, k, off, packed, capacity, self.ws)
+        return off, packed
+
+    def reconstruct(self, packed, packed_elems, off, k):
+        import torch
+        cfg = self.cfg
+        xbar = torch.full((cfg.n, cfg.d), 3.0, dtype=self.tdt, device="cuda")
+        self.L.dynakv_reconstruct(self.desc, packed, packed_elems, off, k, self.U_inv, xbar, self.ws)
+        return xbar
+
+    def retain(self, k, m, alpha, want_grad=True):
+        import torch
+        cfg = self.cfg
+        out = torch.zeros(3, dtype=torch.float32, device="cuda")
+        g = torch.full((cfg.n, cfg.d), 3.0, dtype=torch.float32, device="cuda") if want_grad else None
+        self.L.dynakv_retain(self.desc, k, m, alpha, out, g, self.ws)
+        return out, g
+
+    def check(self):
+        return self.L.dynakv_check(self.ws)

@@ -1,0 +1,184 @@
+"""GPU parity of the KV-compression path (include/dynakv.h) against the fp64 oracle on the same seeded
+inputs, through the C ABI.
+
+Tolerances.  Integer and byte work (segment offsets, the packed layout, zero fill) is compared
+bit-exactly on inputs the oracle also sees.  The spectral state is rounded to the storage type from
+an fp32 accumulator here and from fp64 in the oracle, so single elements may land on the neighbouring
+bf16 value (|d| <= one unit in the last place); such a flip moves that token's gate logits by up to
+~1e-2 and its mask by a few 1e-3.  Hence: x~ within one ulp of the storage type and equal on > 99 %
+of the elements; |dm| <= 5e-3 (bf16) / 1e-4 (fp32); the retained count k must be a valid threshold
+crossing of the oracle's mask under that tolerance everywhere, and equal to the oracle's wherever
+the oracle's mask clears tau by more than the tolerance; reconstruction within 1e-2 relative
+Frobenius error (the bound used for the other matrix outputs of this library).
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+import workloads.dynakv as kv
+from oracle import dynakv_oracle as O
+from tests.harness import KvProblem, np64, rel_fro, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _tols(cfg):
+    return (2.0 ** -7, 5e-3) if cfg.dtype == "bf16" else (2.0 ** -22, 1e-4)
+
+
+def _oracle_chain(cfg, inp, tau, order="suffix"):
+    f = wl.as_f64
+    g = O.gate(f(inp["x"]), f(inp["U"]), f(inp["W"]), inp["b"], tau, order=order, store_dtype=cfg.dtype)
+    off, packed = O.store(g["xt"], g["k"])
+    g["off"], g["packed"] = off, packed
+    g["xbar"] = O.reconstruct(packed, off, g["k"], f(inp["U_inv"]), store_dtype=cfg.dtype)
+    return g
+
+
+def _check_k(k_gpu, o, tau, tol, d):
+    """k_gpu is a valid crossing of the oracle's mask, and the oracle's own wherever that is unambiguous."""
+    m = o["m"]
+    n = m.shape[0]
+    rows = np.arange(n)
+    assert np.all((k_gpu >= 1) & (k_gpu <= d))
+    last_kept = m[rows, k_gpu - 1]
+    first_cut = np.where(k_gpu < d, m[rows, np.minimum(k_gpu, d - 1)], -1.0)
+    assert np.all(last_kept > tau - tol) and np.all(first_cut <= tau + tol)
+    ko = o["k"].astype(np.int64)
+    margin = np.minimum(m[rows, ko - 1] - tau, np.where(ko < d, tau - m[rows, np.minimum(ko, d - 1)], 1.0))
+    clear = margin > tol
+    assert np.array_equal(k_gpu[clear], ko[clear])
+    return float(np.mean(k_gpu == ko)), float(np.mean(clear))
+
+
+def _gate_parity(cfg, inp, tau, flags=0, order="suffix", ldx=None):
+    ulp, tol_m = _tols(cfg)
+    o = _oracle_chain(cfg, inp, tau, order)
+    kp = KvProblem(cfg, inp, flags=flags, ldx=ldx)
+    xt, k, m, xhat = kp.gate(tau)
+    assert kp.check() == 0
+    g_xt, g_m, g_xhat = np64(xt), np64(m), np64(xhat)
+    assert np.all(np.abs(g_xt - o["xt"]) <= ulp * np.abs(o["xt"]) + 1e-30)
+    assert np.mean(g_xt == o["xt"]) > 0.99
+    assert np.abs(g_m - o["m"]).max() <= tol_m
+    assert np.all(np.diff(g_m, axis=1) <= 1e-6) and np.abs(g_m[:, 0] - 1).max() <= 1e-5
+    assert np.all(np.abs(g_xhat - o["xhat"]) <= ulp * np.abs(o["xhat"]) + tol_m * np.abs(o["xt"]) + 1e-30)
+    k_gpu = k.cpu().numpy().astype(np.int64)
+    same, clear = _check_k(k_gpu, o, tau, tol_m, cfg.d)
+    # without the training outputs the same counts come back
+    xt2, k2, _, _ = kp.gate(tau, soft=False)
+    assert np.array_equal(k2.cpu().numpy(), k.cpu().numpy()) and bool((xt2 == xt).all())
+    return kp, o, (xt, k, m, xhat), same, clear
+
+
+def test_tiny_fp32_chain_end_to_end():
+    cfg = kv.KV_CONFIGS[0]
+    inp = kv.kv_inputs(cfg)
+    kp, o, (xt, k, m, xhat), same, clear = _gate_parity(cfg, inp, cfg.tau)
+    assert same > 0.99 and clear > 0.95
+    off, packed = kp.store(xt, k)
+    total = int(off[-1].item())
+    xbar = kp.reconstruct(packed, total, off, k)
+    assert kp.check() == 0
+    assert rel_fro(np64(xbar), o["xbar"]) <= 1e-4
+    out, g = kp.retain(k, m, 0.5)
+    pen, Rs, grad = O.retain_penalty(o["m"], 0.5)
+    got = np64(out)
+    assert abs(got[0] - O.retain_rate_hard(o["k"], cfg.d)) <= 2e-3       # a few counts may differ by one
+    assert abs(got[1] - Rs) <= 1e-5 and abs(got[2] - pen) <= 1e-5
+    assert np.abs(np64(g) - grad).max() <= 1e-6 * np.abs(grad).max()
+
+
+@pytest.mark.parametrize("literal", [False, True])
+def test_small_bf16_gate_both_mask_orders(literal):
+    cfg = kv.KV_CONFIGS[1]
+    inp = kv.kv_inputs(cfg)
+    flags = 1 if literal else 0
+    kp, o, outs, same, clear = _gate_parity(cfg, inp, cfg.tau, flags=flags, order="literal" if literal else "suffix")
+    assert same > 0.9
+    if literal:
+        # the two readings differ: the printed formula keeps the complement count on a one-hot gate
+        o2 = _oracle_chain(cfg, inp, cfg.tau, "suffix")
+        assert np.mean(o2["k"] == o["k"]) < 0.5
+
+
+def test_small_bf16_chain_end_to_end_with_strided_input():
+    cfg = kv.KV_CONFIGS[1].scaled(n=777, d=320)       # d with a ragged last tile and last position group
+    inp = kv.kv_inputs(cfg)
+    kp, o, (xt, k, m, xhat), same, clear = _gate_parity(cfg, inp, cfg.tau, ldx=cfg.d + 24)
+    off, packed = kp.store(xt, k)
+    xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
+    assert kp.check() == 0
+    assert rel_fro(np64(xbar), o["xbar"]) <= 1e-2
+    out, _ = kp.retain(k, m, 0.3, want_grad=False)
+    assert abs(np64(out)[0] - O.retain_rate_hard(o["k"], cfg.d)) <= 2e-3
+    assert abs(np64(out)[1] - O.retain_rate_soft(o["m"])) <= 1e-3
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_store_and_reconstruct_from_oracle_inputs_are_exact(dtype):
+    """The store is byte work: fed with the oracle's own (rounded) x~ and k it must reproduce the oracle's
+    offsets and packed array bit for bit, including counts 0 and d; the reconstruction of that store
+    matches the oracle's to rounding."""
+    cfg = kv.KV_CONFIGS[1].scaled(n=613, d=256, dtype=dtype)
+    inp = kv.kv_inputs(cfg)
+    o = _oracle_chain(cfg, inp, cfg.tau)
+    k = o["k"].copy()
+    k[[0, 5, 612]] = 0
+    k[[1, 300]] = cfg.d
+    k[2], k[3], k[4] = 1, 8, 9
+    off, packed = O.store(o["xt"], k)
+    xbar = O.reconstruct(packed, off, k, wl.as_f64(inp["U_inv"]), store_dtype=dtype)
+    kp = KvProblem(cfg, inp)
+    as_store = (lambda a: wl.bf16_bits_from_f32(a.astype(np.float32))) if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    d_xt, d_k = to_device(as_store(o["xt"])), to_device(k.astype(np.int32))
+    g_off, g_packed = kp.store(d_xt, d_k)
+    assert kp.check() == 0
+    assert np.array_equal(g_off.cpu().numpy(), off)
+    assert np.array_equal(np64(g_packed)[: off[-1]], packed)
+    assert bool((g_packed[off[-1]:] == 5.0).all())                  # nothing written past the end
+    g_xbar = kp.reconstruct(g_packed, int(off[-1]), g_off, d_k)
+    assert kp.check() == 0
+    got = np64(g_xbar)
+    assert np.all(got[k == 0] == 0)
+    assert rel_fro(got, xbar) <= (2e-3 if dtype == "bf16" else 1e-5)
+    # a permuted token order in the store (offsets need not increase with the token index)
+    perm_off = off[:-1].copy()
+    g_xbar2 = kp.reconstruct(g_packed, int(off[-1]), to_device(np.append(perm_off, off[-1])), d_k)
+    assert bool((g_xbar2 == g_xbar).all())
+
+
+def test_nothing_pruned_round_trip_and_everything_pruned():
+    cfg = kv.KV_CONFIGS[0].scaled(n=130, d=64)
+    inp = kv.kv_inputs(cfg)
+    kp = KvProblem(cfg, inp)
+    xt, k, m, _ = kp.gate(0.0)                                      # tau = 0 keeps every component
+    assert bool((k == cfg.d).all())
+    off, packed = kp.store(xt, k)
+    xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
+    # U_inv is the inverse of U up to fp32 rounding, so the round trip returns x
+    assert rel_fro(np64(xbar), wl.as_f64(inp["x"])) <= 1e-4
+    xt, k, m, _ = kp.gate(1.0)                                      # nothing exceeds tau = 1 except rounding
+    assert bool((k <= 1).all())
+
+
+def test_device_side_errors_are_reported():
+    import torch
+    cfg = kv.KV_CONFIGS[0].scaled(n=40, d=64)
+    inp = kv.kv_inputs(cfg)
+    kp = KvProblem(cfg, inp)
+    xt, k, _, _ = kp.gate(cfg.tau, soft=False)
+    off, packed = kp.store(xt, k)
+    assert kp.check() == 0
+    total = int(off[-1].item())
+    off2, packed2 = kp.store(xt, k, capacity=total - 8)             # the last segment does not fit
+    assert kp.check() == -6
+    assert bool((off2 == off).all())
+    bad_k = k.clone()
+    bad_k[3] = cfg.d + 1
+    kp.store(xt, bad_k)
+    assert kp.check() == -6
+    kp.reconstruct(packed, total - 8, off, k)                       # offsets point past the readable part
+    assert kp.check() == -6
+    kp.reconstruct(packed, total, off, k)
+    assert kp.check() == 0

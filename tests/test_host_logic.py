@@ -24,12 +24,15 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "lmhead.h")).read()
-    declared = re.findall(r"LMHEAD_API\s+[\w\s\*]+?\b(\w+)\s*\(", header)
-    assert len(declared) >= 12
-    for name in declared:
-        assert hasattr(lib, name), f"{name} is declared in lmhead.h but not exported"
-    assert sorted(declared) == sorted(L.EXPORTED_SYMBOLS)
+    declared = []
+    for name, symbols in (("lmhead.h", L.EXPORTED_SYMBOLS), ("dynakv.h", L.DYNAKV_SYMBOLS)):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        here = re.findall(r"LMHEAD_API\s+[\w\s\*]+?\b(\w+)\s*\(", header)
+        assert len(here) >= 7
+        for sym in here:
+            assert hasattr(lib, sym), f"{sym} is declared in {name} but not exported"
+        assert sorted(here) == sorted(symbols)
+        declared += here
     assert lib.lmhead_abi_version() == 1
     # nothing but the C ABI is exported
     out = subprocess.run(["nm", "-D", "--defined-only", L.library_path()], capture_output=True, text=True).stdout
@@ -98,6 +101,44 @@ def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
     ms, n = C.c_double(), C.c_int64()
     assert lib.lmhead_timing_read(9, C.byref(ms), C.byref(n)) == -2
     assert lib.lmhead_timing_read(0, None, C.byref(n)) == -1
+
+
+def test_dynakv_descriptor_and_argument_validation(lib):
+    from paper_2603_04411_amd import dynakv as K
+    assert C.sizeof(K.DynakvDesc) == 4 * 4 + 2 * 8 and K.DynakvDesc.ldx.offset == 16
+    ok = L.make_kv_desc(1000, 512, "bf16")
+    assert L.dynakv_validate_desc(ok) == 0
+    need = L.dynakv_workspace_bytes(ok)
+    assert need > 1000 * 512 * 4        # holds the fp32 gate logits
+    cases = [
+        (dict(n=0), -2), (dict(d=0), -2), (dict(d=100), -2), (dict(d=16384), -2), (dict(dtype=5), -3),
+        (dict(flags=2), -3), (dict(ldx=256), -2), (dict(ldx=516), -4), (dict(n=1 << 22), -2),
+    ]
+    for change, code in cases:
+        kw = dict(n=1000, d=512, dtype="bf16")
+        kw.update(change)
+        desc = L.make_kv_desc(**kw)
+        assert L.dynakv_validate_desc(desc) == code, (change, L.dynakv_validate_desc(desc))
+        assert L.dynakv_workspace_bytes(desc) == 0
+    assert lib.dynakv_validate_desc(None) == -1
+    p = 0x10000   # never dereferenced
+    d = C.byref(ok)
+    gate, store, rec, ret = lib.dynakv_gate, lib.dynakv_store, lib.dynakv_reconstruct, lib.dynakv_retain
+    assert gate(d, None, p, p, p, 0.1, p, p, None, None, p, need, None) == -1
+    assert gate(d, p, p, p, p, 0.1, p, None, None, None, p, need, None) == -1
+    assert gate(d, p, p + 2, p, p, 0.1, p, p, None, None, p, need, None) == -4
+    assert gate(d, p, p, p, p, 0.1, p, p, None, None, p + 16, need, None) == -4
+    assert gate(d, p, p, p, p, 0.1, p, p, None, None, p, need - 1, None) == -5
+    assert gate(d, p, p, p, p, 0.1, p, p, None, None, None, need, None) == -1
+    assert store(d, p, p, None, p, 1 << 20, p, need, None) == -1
+    assert store(d, p, p, p, p, -1, p, need, None) == -2
+    assert store(d, p, p, p + 4, p, 1 << 20, p, need, None) == -4
+    assert rec(d, p, 1 << 20, p, p, None, p, p, need, None) == -1
+    assert rec(d, p, 1 << 31, p, p, p, p, p, need, None) == -2       # more than 2^31 bytes of bf16
+    assert rec(d, p, 1 << 20, p, p, p, p, p, 100, None) == -5
+    assert ret(d, p, p, 0.5, None, None, p, need, None) == -1
+    assert ret(d, p, p + 4, 0.5, p, None, p, need, None) == -4
+    assert lib.dynakv_check(None, None) == -1
 
 
 def test_workspace_grows_with_the_problem_and_default_chunk_is_bounded():
