@@ -83,6 +83,18 @@ def cpu_baseline(cfg, H_host, W_host, tok, lens, sample_rows: int, gpu_logp=None
 
 
 def main() -> int:
+    if "--workload" in sys.argv:
+        # the widened path has its own step, metric and roofline: bench.py --workload dynakv [...]
+        i = sys.argv.index("--workload")
+        which = sys.argv[i + 1] if i + 1 < len(sys.argv) else ""
+        rest = sys.argv[1:i] + sys.argv[i + 2:]
+        if which == "dynakv":
+            import bench_dynakv
+            return bench_dynakv.main(rest)
+        if which != "lmhead":
+            print(f"bench.py: unknown workload {which!r} (lmhead | dynakv)", file=sys.stderr)
+            return 2
+        sys.argv = [sys.argv[0]] + rest
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)

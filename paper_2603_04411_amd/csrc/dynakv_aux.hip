@@ -56,9 +56,11 @@ struct Store4<__bf16> {
 // One wavefront per token.  Mask position i belongs to gate column j(i) = i (reverse cumulative
 // sum) or j(i) = d-1-i (Eq. 6 as printed: Flip(cumsum(p))_i = sum_{i' >= i} p_{d-1-i'}), so both
 // readings are the same suffix sum over positions.  Positions are walked in groups of 256 (four
-// per lane, contiguous), last group first, carrying the running suffix.  The row of logits
-// (4 KB at d = 1024) is read three times (max, sum, suffix); the second and third read hit L1/L2.
-template <typename T>
+// per lane, contiguous), last group first, carrying the running suffix.
+// NG > 0: the row has NG groups (d <= 256 NG) and is held in registers: one pass over memory.
+// NG == 0: any d; the row of logits is read three times (max, sum, suffix), the second and third
+// time from L1/L2.
+template <typename T, int NG>
 __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ logits,
                                                       const float* __restrict__ bias,
                                                       const T* __restrict__ xt, int64_t n, int d, float tau,
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
   const int64_t tok = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tok >= n) return;
   const float* z = logits + tok * d;
-  const int ngroups = (d + 255) / 256;
+  const int ngroups = NG > 0 ? NG : (d + 255) / 256;
 
   // logits (+ bias) of the four positions that start at i0, in position order
   auto load4 = [&](int i0, float (&v)[4]) {
@@ -84,24 +86,46 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
     }
   };
 
+  constexpr int NR = NG > 0 ? NG : 1;
+  float row[NR][4];
   float mx = -__builtin_huge_valf();
-  for (int g = 0; g < ngroups; ++g) {
-    const int i0 = g * 256 + lane * 4;
-    if (i0 < d) {
-      float v[4];
-      load4(i0, v);
-      mx = fmaxf(fmaxf(mx, fmaxf(v[0], v[1])), fmaxf(v[2], v[3]));
-    }
-  }
-  mx = wave_max(mx);
   float sum = 0.f;
-  for (int g = 0; g < ngroups; ++g) {
-    const int i0 = g * 256 + lane * 4;
-    if (i0 < d) {
-      float v[4];
-      load4(i0, v);
+  if constexpr (NG > 0) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+    for (int g = 0; g < NG; ++g) {
+      const int i0 = g * 256 + lane * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) row[g][e] = -__builtin_huge_valf();
+      if (i0 < d) load4(i0, row[g]);
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) mx = fmaxf(fmaxf(mx, fmaxf(row[g][0], row[g][1])), fmaxf(row[g][2], row[g][3]));
+    mx = wave_max(mx);
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        row[g][e] = __builtin_amdgcn_exp2f((row[g][e] - mx) * kLog2e);   // exp(-inf) = 0 beyond d
+        sum += row[g][e];
+      }
+  } else {
+    for (int g = 0; g < ngroups; ++g) {
+      const int i0 = g * 256 + lane * 4;
+      if (i0 < d) {
+        float v[4];
+        load4(i0, v);
+        mx = fmaxf(fmaxf(mx, fmaxf(v[0], v[1])), fmaxf(v[2], v[3]));
+      }
+    }
+    mx = wave_max(mx);
+    for (int g = 0; g < ngroups; ++g) {
+      const int i0 = g * 256 + lane * 4;
+      if (i0 < d) {
+        float v[4];
+        load4(i0, v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+      }
     }
   }
   sum = wave_sum(sum);
@@ -109,20 +133,14 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
 
   float carry = 0.f;   // sum of exp over all positions after the current group
   int count = 0;
-  for (int g = ngroups - 1; g >= 0; --g) {
+  // one group: s[] = the lane's four exponentials in position order
+  auto group = [&](int g, float (&s)[4]) {
     const int i0 = g * 256 + lane * 4;
     const bool on = i0 < d;
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    if (on) {
-      float v[4];
-      load4(i0, v);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) s[e] = __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
-      s[2] += s[3];
-      s[1] += s[2];
-      s[0] += s[1];
-    }
-    // inclusive suffix sum of the lanes' totals (lanes above this one)
+    s[2] += s[3];
+    s[1] += s[2];
+    s[0] += s[1];
+    // inclusive suffix sum of the lanes' totals (this lane and the lanes above it)
     float incl = s[0];
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -146,6 +164,22 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
         for (int e = 0; e < 4; ++e) xv[e] *= mk[e];
         Store4<T>::store(xhat + tok * d + i0, xv);
       }
+    }
+  };
+  if constexpr (NG > 0) {
+#pragma unroll
+    for (int g = NG - 1; g >= 0; --g) group(g, row[g]);
+  } else {
+    for (int g = ngroups - 1; g >= 0; --g) {
+      const int i0 = g * 256 + lane * 4;
+      float s[4] = {0.f, 0.f, 0.f, 0.f};
+      if (i0 < d) {
+        float v[4];
+        load4(i0, v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] = __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+      }
+      group(g, s);
     }
   }
   count = wave_sum_i(count);
@@ -291,17 +325,35 @@ __global__ void kv_bucket_start_kernel(int32_t* __restrict__ hist, int nbuckets)
   }
 }
 
-// The position inside a bucket comes from an integer atomic, so `order` may differ from run to run
-// within a bucket; the reconstruction's results do not depend on it (a token's output only
-// involves its own row, and extra K-steps of a tile add exact zeros).
+// The position inside a bucket comes from integer atomics (a rank inside the workgroup's 4096 tokens
+// from LDS, one global reservation per workgroup and bucket), so `order` may differ from run to run
+// within a bucket; the reconstruction's results do not depend on it (a token's output only involves
+// its own row, and extra K-steps of a tile add exact zeros).
 __global__ __launch_bounds__(256) void kv_scatter_kernel(const int32_t* __restrict__ k, int64_t n, int d, int esz,
                                                          int nbuckets, int32_t* __restrict__ hist,
                                                          int32_t* __restrict__ order) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  const int b = bucket_of(k[i], d, esz);
-  const int pos = atomicAdd(&hist[2 * nbuckets + b], 1);
-  order[hist[nbuckets + b] + pos] = (int32_t)i;
+  extern __shared__ int32_t h[];   // [nbuckets] counts, then [nbuckets] bases
+  constexpr int PER = 16;          // tokens per thread
+  for (int i = threadIdx.x; i < nbuckets; i += 256) h[i] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * (256 * PER);
+  int bk[PER], rank[PER];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int64_t i = base + j * 256 + threadIdx.x;
+    bk[j] = -1;
+    if (i < n) {
+      bk[j] = bucket_of(k[i], d, esz);
+      rank[j] = atomicAdd(&h[bk[j]], 1);
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < nbuckets; b += 256)
+    h[nbuckets + b] = hist[nbuckets + b] + (h[b] ? atomicAdd(&hist[2 * nbuckets + b], h[b]) : 0);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < PER; ++j)
+    if (bk[j] >= 0) order[h[nbuckets + bk[j]] + rank[j]] = (int32_t)(base + j * 256 + threadIdx.x);
 }
 
 // ---- retain rate ----------------------------------------------------------------------------
@@ -388,15 +440,33 @@ hipError_t launch_kv_clear_header(WsHeader* hdr, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <typename T>
+static void launch_mask_t(const float* logits, const float* b, const void* xt, int64_t n, int d, float tau,
+                          bool literal, int32_t* k, float* m, void* xhat, hipStream_t s) {
+  const dim3 grid((unsigned)((n + 3) / 4));
+  const T* x = static_cast<const T*>(xt);
+  T* xh = static_cast<T*>(xhat);
+  const int lit = literal ? 1 : 0;
+  const int ng = (d + 255) / 256;
+#define KV_MASK(NG) hipLaunchKernelGGL((kv_mask_kernel<T, NG>), grid, dim3(256), 0, s, logits, b, x, n, d, tau, lit, k, m, xh)
+  switch (ng) {
+    case 1: KV_MASK(1); break;
+    case 2: KV_MASK(2); break;
+    case 3: KV_MASK(3); break;
+    case 4: KV_MASK(4); break;
+    case 5: case 6: KV_MASK(6); break;
+    case 7: case 8: KV_MASK(8); break;
+    default: KV_MASK(0); break;
+  }
+#undef KV_MASK
+}
+
 hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const void* xt, int64_t n, int d,
                           float tau, bool literal, int32_t* k, float* m, void* xhat, hipStream_t s) {
-  const dim3 grid((unsigned)((n + 3) / 4));
   if (dtype == LMHEAD_BF16)
-    hipLaunchKernelGGL(kv_mask_kernel<__bf16>, grid, dim3(256), 0, s, logits, b, static_cast<const __bf16*>(xt), n,
-                       d, tau, literal ? 1 : 0, k, m, static_cast<__bf16*>(xhat));
+    launch_mask_t<__bf16>(logits, b, xt, n, d, tau, literal, k, m, xhat, s);
   else
-    hipLaunchKernelGGL(kv_mask_kernel<float>, grid, dim3(256), 0, s, logits, b, static_cast<const float*>(xt), n, d,
-                       tau, literal ? 1 : 0, k, m, static_cast<float*>(xhat));
+    launch_mask_t<float>(logits, b, xt, n, d, tau, literal, k, m, xhat, s);
   return hipGetLastError();
 }
 
@@ -426,8 +496,8 @@ hipError_t launch_kv_order(int dtype, const int32_t* k, int64_t n, int64_t ncap,
   hipLaunchKernelGGL(kv_hist_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256), nbuckets * sizeof(int32_t), s,
                      k, n, d, esz, nbuckets, hist);
   hipLaunchKernelGGL(kv_bucket_start_kernel, dim3(1), dim3(64), 0, s, hist, nbuckets);
-  hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, k, n, d, esz, nbuckets,
-                     hist, order);
+  hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256),
+                     2 * nbuckets * sizeof(int32_t), s, k, n, d, esz, nbuckets, hist, order);
   return hipGetLastError();
 }
 

@@ -5,8 +5,8 @@ Tolerances.  Integer and byte work (segment offsets, the packed layout, zero fil
 bit-exactly on inputs the oracle also sees.  The spectral state is rounded to the storage type from
 an fp32 accumulator here and from fp64 in the oracle, so single elements may land on the neighbouring
 bf16 value (|d| <= one unit in the last place); such a flip moves that token's gate logits by up to
-~1e-2 and its mask by a few 1e-3.  Hence: x~ within one ulp of the storage type and equal on > 99 %
-of the elements; |dm| <= 5e-3 (bf16) / 1e-4 (fp32); the retained count k must be a valid threshold
+~1e-2 and its mask by a few 1e-3.  Hence: x~ within one ulp of the storage type (plus the fp32
+accumulation error, 1e-6 of the largest entry) and, for bf16, equal on > 99 % of the elements; |dm| <= 5e-3 (bf16) / 1e-4 (fp32); the retained count k must be a valid threshold
 crossing of the oracle's mask under that tolerance everywhere, and equal to the oracle's wherever
 the oracle's mask clears tau by more than the tolerance; reconstruction within 1e-2 relative
 Frobenius error (the bound used for the other matrix outputs of this library).
@@ -58,11 +58,13 @@ def _gate_parity(cfg, inp, tau, flags=0, order="suffix", ldx=None):
     xt, k, m, xhat = kp.gate(tau)
     assert kp.check() == 0
     g_xt, g_m, g_xhat = np64(xt), np64(m), np64(xhat)
-    assert np.all(np.abs(g_xt - o["xt"]) <= ulp * np.abs(o["xt"]) + 1e-30)
-    assert np.mean(g_xt == o["xt"]) > 0.99
+    acc = 1e-6 * np.abs(o["xt"]).max()          # fp32 accumulation error scales with the row, not the element
+    assert np.all(np.abs(g_xt - o["xt"]) <= ulp * np.abs(o["xt"]) + acc)
+    if cfg.dtype == "bf16":
+        assert np.mean(g_xt == o["xt"]) > 0.99
     assert np.abs(g_m - o["m"]).max() <= tol_m
     assert np.all(np.diff(g_m, axis=1) <= 1e-6) and np.abs(g_m[:, 0] - 1).max() <= 1e-5
-    assert np.all(np.abs(g_xhat - o["xhat"]) <= ulp * np.abs(o["xhat"]) + tol_m * np.abs(o["xt"]) + 1e-30)
+    assert np.all(np.abs(g_xhat - o["xhat"]) <= ulp * np.abs(o["xhat"]) + tol_m * np.abs(o["xt"]) + acc)
     k_gpu = k.cpu().numpy().astype(np.int64)
     same, clear = _check_k(k_gpu, o, tau, tol_m, cfg.d)
     # without the training outputs the same counts come back
@@ -142,10 +144,18 @@ def test_store_and_reconstruct_from_oracle_inputs_are_exact(dtype):
     got = np64(g_xbar)
     assert np.all(got[k == 0] == 0)
     assert rel_fro(got, xbar) <= (2e-3 if dtype == "bf16" else 1e-5)
-    # a permuted token order in the store (offsets need not increase with the token index)
-    perm_off = off[:-1].copy()
-    g_xbar2 = kp.reconstruct(g_packed, int(off[-1]), to_device(np.append(perm_off, off[-1])), d_k)
-    assert bool((g_xbar2 == g_xbar).all())
+    # segments laid out in reverse token order: offsets need not increase with the token index
+    seg = np.diff(off)
+    rev_off = np.zeros(cfg.n + 1, dtype=np.int64)
+    rev_packed = np.zeros(int(off[-1]), dtype=np.float64)
+    pos = 0
+    for i in range(cfg.n - 1, -1, -1):
+        rev_off[i] = pos
+        rev_packed[pos: pos + seg[i]] = packed[off[i]: off[i + 1]]
+        pos += seg[i]
+    rev_off[cfg.n] = pos
+    g_xbar2 = kp.reconstruct(to_device(as_store(rev_packed)), pos, to_device(rev_off), d_k)
+    assert kp.check() == 0 and bool((g_xbar2 == g_xbar).all())
 
 
 def test_nothing_pruned_round_trip_and_everything_pruned():
@@ -158,8 +168,12 @@ def test_nothing_pruned_round_trip_and_everything_pruned():
     xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
     # U_inv is the inverse of U up to fp32 rounding, so the round trip returns x
     assert rel_fro(np64(xbar), wl.as_f64(inp["x"])) <= 1e-4
-    xt, k, m, _ = kp.gate(1.0)                                      # nothing exceeds tau = 1 except rounding
-    assert bool((k <= 1).all())
+    xt, k, m, _ = kp.gate(1.001)                                    # no mask value exceeds 1 (up to rounding)
+    assert bool((k == 0).all())
+    off, packed = kp.store(xt, k)
+    assert bool((off == 0).all()) and kp.check() == 0
+    xbar = kp.reconstruct(packed, 0, off, k)                        # an empty store reconstructs to zeros
+    assert kp.check() == 0 and bool((xbar == 0).all())
 
 
 def test_device_side_errors_are_reported():
@@ -182,3 +196,56 @@ def test_device_side_errors_are_reported():
     assert kp.check() == -6
     kp.reconstruct(packed, total, off, k)
     assert kp.check() == 0
+
+
+def test_full_size_stream_sampled_against_the_oracle():
+    """One layer's key stream at benchmark size (262144 tokens, d_kv = 1024), in the launch
+    configuration the benchmark times: a seeded sample of tokens is checked against the oracle row by
+    row, and the whole result against properties that hold at any size."""
+    import torch
+    cfg = kv.KV_CONFIGS[2]
+    inp = kv.kv_inputs(cfg)
+    kp = KvProblem(cfg, inp)
+    xt, k, _, _ = kp.gate(cfg.tau, soft=False)
+    off, packed = kp.store(xt, k)
+    total = int(off[-1].item())
+    xbar = kp.reconstruct(packed, total, off, k)
+    assert kp.check() == 0
+    n, d = cfg.n, cfg.d
+    k_h, off_h = k.cpu().numpy().astype(np.int64), off.cpu().numpy()
+    # integer structure of the whole store
+    assert k_h.min() >= 1 and k_h.max() <= d
+    seg = (k_h + 7) // 8 * 8
+    assert off_h[0] == 0 and np.array_equal(np.diff(off_h), seg) and total == seg.sum()
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.random.default_rng(7).integers(0, n, 700), [n - 1]]))
+    # packed segments are the leading components of the spectral state, zero padded
+    xt_h = np64(xt[torch.from_numpy(rows).cuda()])
+    for r, i in enumerate(rows):
+        segv = np64(packed[off_h[i]: off_h[i + 1]])
+        assert np.array_equal(segv[: k_h[i]], xt_h[r, : k_h[i]]) and np.all(segv[k_h[i]:] == 0)
+    # sampled tokens against the oracle (every token is independent of the others)
+    sub = {key: (inp[key][rows] if key == "x" else inp[key]) for key in inp}
+    o = _oracle_chain(cfg.scaled(n=rows.size), sub, cfg.tau)
+    ulp, tol_m = _tols(cfg)
+    assert np.all(np.abs(xt_h - o["xt"]) <= ulp * np.abs(o["xt"]) + 1e-6 * np.abs(o["xt"]).max())
+    same, clear = _check_k(k_h[rows], o, cfg.tau, tol_m, d)
+    assert same > 0.9
+    got = np64(xbar[torch.from_numpy(rows).cuda()])
+    assert rel_fro(got, o["xbar"]) <= 1e-2
+    # the reconstruction error of every token is the energy it discarded, up to rounding: U is close to
+    # orthogonal here, so ||x - x_bar||^2 ~ sum_{j >= k} x~_j^2 (checked in aggregate over the sample)
+    x_s = wl.as_f64(inp["x"][rows])
+    tail = np.array([(o["xt"][r, k_h[i]:] ** 2).sum() for r, i in enumerate(rows)])
+    err = ((x_s - got) ** 2).sum(1)
+    assert abs(err.sum() - tail.sum()) <= 0.1 * tail.sum() + 1e-3 * (x_s ** 2).sum()
+
+
+def test_wide_state_uses_the_multi_pass_mask_kernel():
+    # d_kv beyond 2048 takes the mask kernel's generic (three-pass) path; 9 tiles along d
+    cfg = kv.KV_CONFIGS[1].scaled(n=70, d=2304)
+    inp = kv.kv_inputs(cfg)
+    kp, o, (xt, k, m, xhat), same, clear = _gate_parity(cfg, inp, cfg.tau)
+    off, packed = kp.store(xt, k)
+    xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
+    assert kp.check() == 0
+    assert rel_fro(np64(xbar), o["xbar"]) <= 1e-2
