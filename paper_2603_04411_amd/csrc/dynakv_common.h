@@ -74,6 +74,7 @@ struct KvGemmArgs {
   float* out_f;
   int64_t ldo;
   WsHeader* hdr;
+  int walk_len;         // set by the launcher: length of the tile walk (tile_map.h)
 };
 hipError_t launch_kv_gemm(int dtype, const KvGemmArgs& a, hipStream_t s);
 

@@ -20,18 +20,32 @@ namespace {
 
 constexpr int kKvMapBx = 4, kKvMapBy = 4;
 
+// Compute units of the current device (256 on MI355X); asked once.
+int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v >= kNumXcd)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
 template <typename E, bool kMask>
 using KvTile = GemmTile<E, 256, 256, 2, 2, /*kLeadB=*/true, kMask>;
 
+// One output tile; `wg` is the tile's position in the XCD-aware walk.
 template <typename E, int Mode>
-__global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
+__device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   using G = KvTile<E, Mode == 2>;
   constexpr int ESZ = Elem<E>::size;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
   const int mtiles = (a.M + G::BM - 1) / G::BM;
   const int ntiles = (int)((a.Nn + G::BN - 1) / G::BN);
   int mt, nt;
-  if (!xcd_tile_coords(blockIdx.x, mtiles, ntiles, kKvMapBx, kKvMapBy, mt, nt)) return;
+  if (!xcd_tile_coords(wg, mtiles, ntiles, kKvMapBx, kKvMapBy, mt, nt)) return;
   const int64_t n0 = (int64_t)nt * G::BN;
   const int m0 = mt * G::BM;
   const int64_t pitchA = a.ldA * ESZ;
@@ -86,6 +100,13 @@ __global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
     bytesB = 0x7fffffffu;
   }
 
+  // output row of tile column threadIdx.x (fetched now, used after the main loop)
+  int my_row;
+  if constexpr (Mode == 2)
+    my_row = a.order[n0 + threadIdx.x];
+  else
+    my_row = n0 + threadIdx.x < a.Nn ? (int)(n0 + threadIdx.x) : -1;
+
   typename G::Acc acc;
   G::zero(acc);
   G::run_rows(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA, Bbase, offB, limB, bytesB, ksteps,
@@ -96,8 +117,11 @@ __global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
   constexpr int JG = 2;
   constexpr int NCOL = G::WGN * JG * 32;
   constexpr int P = G::BM * 4 + 16;
-  static_assert(NCOL * P <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
+  static_assert(NCOL * P + G::BN * 4 <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
   static_assert(G::BM * 4 / 16 == 64, "one staged row is one wavefront store");
+  static_assert(G::BN == G::NT, "one output row index per thread");
+  int* rows_lds = reinterpret_cast<int*>(smem + NCOL * P);
+  rows_lds[threadIdx.x] = my_row;
 #pragma unroll
   for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
@@ -112,32 +136,54 @@ __global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
           *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
         }
     }
-    __syncthreads();
+    lds_barrier();
+    // The wave streams out staged rows wave, wave + 4, ...  Their output row indices are fetched
+    // once (lane 32 p + i holds the one of iteration i of phase p) and then read with readlane, and
+    // the loop is unrolled in batches whose LDS reads are all issued before the first store, so
+    // that the wave (alone on its SIMD) is not serialised on one LDS round trip per row.
+    constexpr int ROWS_PER_WAVE = NCOL / G::NWAVES;   // per phase
+    static_assert(ROWS_PER_WAVE * (G::TN / JG) == 64, "one output row index per lane");
+    auto tile_col = [&](int phase, int i) {
+      const int r = G::wave() + G::NWAVES * i;
+      return (r / (JG * 32)) * G::WN + phase * (JG * 32) + r % (JG * 32);
+    };
+    if (jg == 0) my_row = rows_lds[tile_col(G::lane() / ROWS_PER_WAVE, G::lane() % ROWS_PER_WAVE)];
     const int c = G::lane();
     const int m = m0 + c * 4;
-#pragma unroll 4
-    for (int r = G::wave(); r < NCOL; r += G::NWAVES) {
-      const int ntl = (r / (JG * 32)) * G::WN + jg * (JG * 32) + r % (JG * 32);   // column within the tile
-      int64_t row = n0 + ntl;
-      if constexpr (Mode == 2) {
-        row = a.order[row];
-      } else {
-        if (row >= a.Nn) row = -1;
-      }
-      if (row < 0 || m >= a.M) continue;
-      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(smem + r * P + c * 16);
-      if (a.out_f) {
-        *reinterpret_cast<f32x4_t*>(a.out_f + row * a.ldo + m) = v;
-      } else if constexpr (ESZ == 4) {
-        *reinterpret_cast<f32x4_t*>(static_cast<float*>(a.out_e) + row * a.ldo + m) = v;
-      } else {
-        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-        const bf16x4_t h = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
-        *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = h;
+    constexpr int RB = 8;
+#pragma unroll
+    for (int i0 = 0; i0 < ROWS_PER_WAVE; i0 += RB) {
+      f32x4_t v[RB];
+#pragma unroll
+      for (int u = 0; u < RB; ++u)
+        v[u] = *reinterpret_cast<const f32x4_t*>(smem + (G::wave() + G::NWAVES * (i0 + u)) * P + c * 16);
+#pragma unroll
+      for (int u = 0; u < RB; ++u) {
+        const int64_t row = __builtin_amdgcn_readlane(my_row, jg * ROWS_PER_WAVE + i0 + u);
+        if (row < 0 || m >= a.M) continue;
+        if (a.out_f) {
+          *reinterpret_cast<f32x4_t*>(a.out_f + row * a.ldo + m) = v[u];
+        } else if constexpr (ESZ == 4) {
+          *reinterpret_cast<f32x4_t*>(static_cast<float*>(a.out_e) + row * a.ldo + m) = v[u];
+        } else {
+          typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+          const bf16x4_t h = {(__bf16)v[u].x, (__bf16)v[u].y, (__bf16)v[u].z, (__bf16)v[u].w};
+          *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = h;
+        }
       }
     }
-    if (jg + 1 < G::TN / JG) __syncthreads();
+    lds_barrier();
   }
+}
+
+// Tiles here are short (d_kv / 64 K-steps or fewer), so the workgroups are persistent: one per
+// compute unit, each taking every gridDim.x-th tile of the walk, which saves a workgroup launch
+// (with all of LDS to hand over) per tile.  gridDim.x is a multiple of 8, so a tile stays on the
+// XCD that the walk meant it for.
+template <typename E, int Mode>
+__global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  for (int wg = blockIdx.x; wg < a.walk_len; wg += gridDim.x) kv_tile<E, Mode>(a, wg, smem);
 }
 
 template <typename E, int Mode>
@@ -145,11 +191,14 @@ hipError_t launch_mode(const KvGemmArgs& a, hipStream_t s) {
   using G = KvTile<E, Mode == 2>;
   const int mtiles = (a.M + G::BM - 1) / G::BM;
   const int64_t ntiles = (a.Nn + G::BN - 1) / G::BN;
-  const dim3 grid(xcd_grid_size(mtiles, ntiles, kKvMapBy));
+  KvGemmArgs b = a;
+  b.walk_len = (int)xcd_grid_size(mtiles, ntiles, kKvMapBy);
+  const unsigned resident = (unsigned)compute_units() / kNumXcd * kNumXcd;   // one workgroup per CU (LDS-bound)
+  const dim3 grid(b.walk_len < (int)resident ? (unsigned)b.walk_len : resident);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_gemm_kernel<E, Mode>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((kv_gemm_kernel<E, Mode>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((kv_gemm_kernel<E, Mode>), grid, dim3(G::NT), G::LDS_BYTES, s, b);
   return hipGetLastError();
 }
 

@@ -84,6 +84,17 @@ constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 constexpr int kWaitVm0 = wait_vm(0);
 constexpr int kWaitLgkm0 = 0xC07F;
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits until every global
+// store issued before it has completed; the epilogues stage a tile through LDS in phases and
+// stream it out with global stores that nothing in the workgroup reads back, so they keep those
+// stores in flight across the barrier instead.
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // kLeadB selects which operand goes first round the LDS ring (see run()).
 // kMaskB: every B row has its own K extent (ragged rows); loads past it fetch zeros (see run()).
 template <typename E, int BM_, int BN_, int WGM_, int WGN_, bool kLeadB = false, bool kMaskB = false>

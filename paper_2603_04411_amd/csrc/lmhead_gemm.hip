@@ -174,7 +174,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       q[2] = tr[j];
     }
   }
-  __syncthreads();
+  lds_barrier();
   for (int n = threadIdx.x; n < G::BN; n += G::NT) {
     float m = red[n * 3], s = red[n * 3 + 1], t = red[n * 3 + 2];
 #pragma unroll
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
           for (int e = 0; e < 4; ++e) Store4<E>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
         }
     }
-    __syncthreads();
+    lds_barrier();
     // [token][vocab] rows -> dZ: one staged row is BM*ESZ contiguous bytes of a dZ row
     {
       constexpr int CPR = G::BM * ESZ / 16;   // 16-byte chunks per row
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
         *reinterpret_cast<u32x4_t*>(dZT + ((size_t)(mrel0 + m) * a.ldZT + n0 + nl) * ESZ) = v;
       }
     }
-    if (jg + 1 < G::TN / JG) __syncthreads();
+    if (jg + 1 < G::TN / JG) lds_barrier();
   }
 }
 
@@ -350,18 +350,38 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
     offB[q] = (uint32_t)(row * pitchB) + G::ld_byte(row);
   }
 
+  // The wave streams out tile columns (output rows) wave, wave + 4, ... of each phase of the epilogue.
+  // Lane 32 p + i fetches the output row of iteration i of phase p now; the epilogue reads it with
+  // readlane instead of one dependent global load per row.
+  constexpr int JG = 2;                           // column blocks (of 32) per wave per phase
+  constexpr int NCOL = G::WGN * JG * 32;          // tile columns (n) staged per phase
+  constexpr int ROWS_PER_WAVE = NCOL / G::NWAVES; // per phase
+  static_assert(ROWS_PER_WAVE * (G::TN / JG) == 64, "one output row index per lane");
+  int my_row;
+  {
+    const int p = G::lane() / ROWS_PER_WAVE, i = G::lane() % ROWS_PER_WAVE;
+    const int r = G::wave() + G::NWAVES * i;
+    const int64_t n = n0 + (r / (JG * 32)) * G::WN + p * (JG * 32) + r % (JG * 32);
+    int64_t row = -1;
+    if (n < n_lim) row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
+    my_row = (int)row;
+  }
+
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA,
          static_cast<const char*>(a.B) + n0 * pitchB, offB, ksteps, smem);
 
   // The fp32 tile leaves through LDS as [n][m] rows, so that each output row segment (BM floats
-  // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.
-  constexpr int JG = 2;                           // column blocks (of 32) per wave per phase
-  constexpr int NCOL = G::WGN * JG * 32;          // tile columns (n) staged per phase
+  // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.  Rows go in
+  // batches: the LDS reads and the loads of the old values of a whole batch are issued before its
+  // first store, so the wave (alone on its SIMD) does not sit out one memory round trip per row.
   constexpr int P = G::BM * 4 + 16;               // staging row pitch in bytes
   static_assert(NCOL * P <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
   static_assert(G::BM * 4 / 16 == 64, "one staged row is one wavefront store");
+  const int c = G::lane();                        // 16-byte chunk of the row = 4 output columns
+  const int m = m0 + c * 4;
+  const bool m_ok = m < a.M;
 #pragma unroll
   for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
@@ -376,22 +396,29 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
           *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
         }
     }
-    __syncthreads();
-    const int c = G::lane();                      // 16-byte chunk of the row = 4 output columns
-    const int m = m0 + c * 4;
-#pragma unroll 4
-    for (int r = G::wave(); r < NCOL; r += G::NWAVES) {
-      const int nt = (r / (JG * 32)) * G::WN + jg * (JG * 32) + r % (JG * 32);   // column within the tile
-      const int64_t n = n0 + nt;
-      if (n >= n_lim) continue;
-      const int64_t row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
-      if (row < 0 || m >= a.M) continue;
-      f32x4_t v = *reinterpret_cast<const f32x4_t*>(smem + r * P + c * 16);
-      f32x4_t* dst = reinterpret_cast<f32x4_t*>(a.out + row * a.ldo + m);
-      if (a.accumulate) v += *dst;
-      *dst = v;
+    lds_barrier();
+    constexpr int RB = 8;
+#pragma unroll
+    for (int i0 = 0; i0 < ROWS_PER_WAVE; i0 += RB) {
+      f32x4_t v[RB], old[RB];
+      f32x4_t* dst[RB];
+#pragma unroll
+      for (int u = 0; u < RB; ++u) {
+        const int64_t row = __builtin_amdgcn_readlane(my_row, jg * ROWS_PER_WAVE + i0 + u);
+        dst[u] = (row >= 0 && m_ok) ? reinterpret_cast<f32x4_t*>(a.out + row * a.ldo + m) : nullptr;
+        v[u] = *reinterpret_cast<const f32x4_t*>(smem + (G::wave() + G::NWAVES * (i0 + u)) * P + c * 16);
+      }
+      if (a.accumulate) {
+#pragma unroll
+        for (int u = 0; u < RB; ++u) old[u] = dst[u] ? *dst[u] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < RB; ++u) v[u] += old[u];
+      }
+#pragma unroll
+      for (int u = 0; u < RB; ++u)
+        if (dst[u]) *dst[u] = v[u];
     }
-    if (jg + 1 < G::TN / JG) __syncthreads();
+    if (jg + 1 < G::TN / JG) lds_barrier();
   }
 }
 
