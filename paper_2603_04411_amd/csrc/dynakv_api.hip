@@ -140,7 +140,8 @@ int dynakv_reconstruct(const dynakv_desc* desc, const void* packed, int64_t pack
   LM_TRY(launch_kv_clear_header(hdr, s));
   // A[j][kk] = U_inv[kk][j]: row j of the copy is output column j, contiguous over the retained index
   LM_TRY(launch_transpose(dt, U_inv, d, d, d, false, hdr, w.at<void>(L.UiT), L.ldT, d, L.dp, s));
-  LM_TRY(launch_kv_order(dt, k, L.n, L.ncap, d, L.nbuckets, w.at<int32_t>(L.hist), w.at<int32_t>(L.order), hdr, s));
+  LM_TRY(launch_kv_order(dt, k, off, packed_elems * L.esz, L.n, L.ncap, d, L.nbuckets, w.at<int32_t>(L.hist),
+                         w.at<int32_t>(L.order), w.at<uint32_t>(L.pos_off), w.at<int32_t>(L.pos_len), hdr, s));
 
   KvGemmArgs ga{};
   ga.mode = 2;
@@ -152,8 +153,8 @@ int dynakv_reconstruct(const dynakv_desc* desc, const void* packed, int64_t pack
   ga.Nn = L.n;
   ga.K = d;
   ga.order = w.at<int32_t>(L.order);
-  ga.off = off;
-  ga.kcnt = k;
+  ga.pos_off = w.at<uint32_t>(L.pos_off);
+  ga.pos_len = w.at<int32_t>(L.pos_len);
   ga.out_e = xbar;
   ga.ldo = d;
   ga.hdr = hdr;

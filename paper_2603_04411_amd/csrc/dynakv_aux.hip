@@ -329,9 +329,14 @@ __global__ void kv_bucket_start_kernel(int32_t* __restrict__ hist, int nbuckets)
 // from LDS, one global reservation per workgroup and bucket), so `order` may differ from run to run
 // within a bucket; the reconstruction's results do not depend on it (a token's output only involves
 // its own row, and extra K-steps of a tile add exact zeros).
-__global__ __launch_bounds__(256) void kv_scatter_kernel(const int32_t* __restrict__ k, int64_t n, int d, int esz,
-                                                         int nbuckets, int32_t* __restrict__ hist,
-                                                         int32_t* __restrict__ order) {
+// Besides the token, each sorted position gets the byte offset and byte length of the token's
+// segment in the store (validated here against the readable extent), so that the reconstruction
+// reads three contiguous arrays instead of chasing order -> off, k.
+__global__ __launch_bounds__(256) void kv_scatter_kernel(const int32_t* __restrict__ k,
+                                                         const int64_t* __restrict__ off, int64_t n, int d, int esz,
+                                                         int64_t bytes, int nbuckets, int32_t* __restrict__ hist,
+                                                         int32_t* __restrict__ order, uint32_t* __restrict__ pos_off,
+                                                         int32_t* __restrict__ pos_len, WsHeader* hdr) {
   extern __shared__ int32_t h[];   // [nbuckets] counts, then [nbuckets] bases
   constexpr int PER = 16;          // tokens per thread
   for (int i = threadIdx.x; i < nbuckets; i += 256) h[i] = 0;
@@ -351,9 +356,23 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(const int32_t* __restri
   for (int b = threadIdx.x; b < nbuckets; b += 256)
     h[nbuckets + b] = hist[nbuckets + b] + (h[b] ? atomicAdd(&hist[2 * nbuckets + b], h[b]) : 0);
   __syncthreads();
+  int bad = 0;
 #pragma unroll
-  for (int j = 0; j < PER; ++j)
-    if (bk[j] >= 0) order[h[nbuckets + bk[j]] + rank[j]] = (int32_t)(base + j * 256 + threadIdx.x);
+  for (int j = 0; j < PER; ++j) {
+    if (bk[j] < 0) continue;
+    const int64_t i = base + j * 256 + threadIdx.x;
+    const int pos = h[nbuckets + bk[j]] + rank[j];
+    const int64_t o = off[i];
+    int dummy = 0;
+    const int seg = seg_len(k[i], d, dummy);
+    order[pos] = (int32_t)i;
+    pos_len[pos] = seg * esz;
+    if (o < 0 || (o & (DYNAKV_GRANULE - 1)) || (o + seg) * esz > bytes)
+      bad = 1;                     // pos_off keeps its fill value: every load of the row is out of range -> zeros
+    else
+      pos_off[pos] = (uint32_t)(o * esz);
+  }
+  if (bad) atomicOr(&hdr->err, kErrKvCapacity);
 }
 
 // ---- retain rate ----------------------------------------------------------------------------
@@ -486,18 +505,23 @@ hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t 
   return hipGetLastError();
 }
 
-hipError_t launch_kv_order(int dtype, const int32_t* k, int64_t n, int64_t ncap, int d, int nbuckets,
-                           int32_t* hist, int32_t* order, WsHeader* hdr, hipStream_t s) {
-  (void)hdr;
+hipError_t launch_kv_order(int dtype, const int32_t* k, const int64_t* off, int64_t bytes, int64_t n, int64_t ncap,
+                           int d, int nbuckets, int32_t* hist, int32_t* order, uint32_t* pos_off, int32_t* pos_len,
+                           WsHeader* hdr, hipStream_t s) {
   const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
+  const unsigned fill_blocks = (unsigned)((ncap + 255) / 256);
   hipLaunchKernelGGL(kv_fill_i32_kernel, dim3((unsigned)((3 * nbuckets + 255) / 256)), dim3(256), 0, s, hist,
                      (int64_t)3 * nbuckets, 0);
-  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3((unsigned)((ncap + 255) / 256)), dim3(256), 0, s, order, ncap, -1);
+  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3(fill_blocks), dim3(256), 0, s, order, ncap, -1);
+  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3(fill_blocks), dim3(256), 0, s, reinterpret_cast<int32_t*>(pos_off),
+                     ncap, (int32_t)0x80000000u);
+  hipLaunchKernelGGL(kv_fill_i32_kernel, dim3(fill_blocks), dim3(256), 0, s, pos_len, ncap, 0);
   hipLaunchKernelGGL(kv_hist_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256), nbuckets * sizeof(int32_t), s,
                      k, n, d, esz, nbuckets, hist);
   hipLaunchKernelGGL(kv_bucket_start_kernel, dim3(1), dim3(64), 0, s, hist, nbuckets);
   hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256),
-                     2 * nbuckets * sizeof(int32_t), s, k, n, d, esz, nbuckets, hist, order);
+                     2 * nbuckets * sizeof(int32_t), s, k, off, n, d, esz, bytes, nbuckets, hist, order, pos_off,
+                     pos_len, hdr);
   return hipGetLastError();
 }
 

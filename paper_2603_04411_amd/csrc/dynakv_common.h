@@ -20,7 +20,7 @@ struct KvLayout {
   int64_t dp;        // d rounded up to the tile
   int64_t ldT;       // pitch (elements) of the transposed parameter copies: d + one 128-byte line
   int nbuckets;      // K-steps a token can need, plus one: d * esz / 128 + 1
-  size_t hdr, UT, WT, UiT, logits, order, hist, blocksum, red, total;
+  size_t hdr, UT, WT, UiT, logits, order, pos_off, pos_len, hist, blocksum, red, total;
 };
 
 static inline KvLayout make_kv_layout(const dynakv_desc* d) {
@@ -44,6 +44,8 @@ static inline KvLayout make_kv_layout(const dynakv_desc* d) {
   L.UiT = take((size_t)L.dp * L.ldT * L.esz);
   L.logits = take((size_t)L.ncap * L.d * 4);
   L.order = take((size_t)L.ncap * 4);
+  L.pos_off = take((size_t)L.ncap * 4);
+  L.pos_len = take((size_t)L.ncap * 4);
   L.hist = take((size_t)L.nbuckets * 3 * 4);          // counts, start positions, cursors
   L.blocksum = take((size_t)(L.ncap / kKvScanBlock + 2) * 8);
   L.red = take((size_t)(L.ncap / 256 + 2) * 2 * 8);   // per-block partial sums of the retain rate
@@ -55,8 +57,9 @@ static inline KvLayout make_kv_layout(const dynakv_desc* d) {
 //   out[row(n)][m] = sum_k A[m][k] * Bop[n][k],  m < M, n < Nn.
 // mode 0/1: Bop rows are dense rows of B (pitch ldB), row(n) = n.  The output is the storage type
 //           (out_e) or fp32 (out_f), whichever is non-null.
-// mode 2:   ragged rows: Bop[n] = packed[off[t] .. off[t] + k[t]) with t = order[n] (order < 0: no
-//           token), zero beyond; row(n) = t; the tile's step count follows its first token.
+// mode 2:   ragged rows: Bop[n] = the pos_len[n] bytes of the packed store at byte offset pos_off[n],
+//           zero beyond; row(n) = order[n] (< 0: no token); the tile's step count follows its
+//           first row, the longest (the three arrays are written by launch_kv_order).
 struct KvGemmArgs {
   int mode;
   const void* A;        // [dp x K] transposed parameter copy, pitch ldA
@@ -67,9 +70,9 @@ struct KvGemmArgs {
   int M;                // output columns (d)
   int64_t Nn;           // tokens
   int K;                // contraction length in elements (d)
-  const int32_t* order; // mode 2
-  const int64_t* off;   // mode 2
-  const int32_t* kcnt;  // mode 2
+  const int32_t* order;     // mode 2
+  const uint32_t* pos_off;  // mode 2
+  const int32_t* pos_len;   // mode 2
   void* out_e;
   float* out_f;
   int64_t ldo;
@@ -88,9 +91,13 @@ hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t 
                            void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr, hipStream_t s);
 
 // order = tokens sorted by descending number of K-steps (ceil(k * esz / 128)), padded with -1 up to
-// ncap.  hist holds 3 * nbuckets ints of scratch.
-hipError_t launch_kv_order(int dtype, const int32_t* k, int64_t n, int64_t ncap, int d, int nbuckets,
-                           int32_t* hist, int32_t* order, WsHeader* hdr, hipStream_t s);
+// ncap; pos_off / pos_len = byte offset and byte length (k rounded up to the granule) of each sorted
+// position's segment in a store of `bytes` readable bytes (0x80000000 / 0 for padding and for
+// segments that do not lie inside it, which also set the error word).  hist holds 3 * nbuckets ints
+// of scratch.
+hipError_t launch_kv_order(int dtype, const int32_t* k, const int64_t* off, int64_t bytes, int64_t n, int64_t ncap,
+                           int d, int nbuckets, int32_t* hist, int32_t* order, uint32_t* pos_off, int32_t* pos_len,
+                           WsHeader* hdr, hipStream_t s);
 
 hipError_t launch_kv_retain(const int32_t* k, const float* m, int64_t n, int d, float alpha, float* out,
                             float* g_m, double* red, hipStream_t s);

@@ -8,9 +8,10 @@
 // per XCD because an XCD runs all M tiles of a token tile together (tile_map.h).
 //
 // Mode 2 reads token rows of differing length straight from the packed store: row n of a tile is
-// the segment of token order[n], loads beyond the segment's end fetch zeros (GemmTile's kMaskB),
-// and the tile runs as many K-steps as its first token needs: `order` lists tokens by descending
-// step count, so that is the tile's maximum and tiles of short tokens are short.
+// the segment of token order[n] (its byte offset and length come with it in pos_off / pos_len),
+// loads beyond the segment's end fetch zeros (GemmTile's kMaskB), and the tile runs as many
+// K-steps as its first token needs: `order` lists tokens by descending step count, so that is
+// the tile's maximum and tiles of short tokens are short.
 #include "dynakv_common.h"
 #include "gemm_core.h"
 
@@ -61,29 +62,13 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   uint32_t bytesB;
   int ksteps;
   if constexpr (Mode == 2) {
-    int bad = 0;
 #pragma unroll
     for (int q = 0; q < G::B_LD; ++q) {
       const int row = G::ldB_row(q);
-      const int t = a.order[n0 + row];
-      offB[q] = 0x80000000u;
-      limB[q] = 0;
-      if (t >= 0) {
-        const int64_t o = a.off[t];
-        const int kk = min(max(a.kcnt[t], 0), a.M);
-        const int seg = (kk + DYNAKV_GRANULE - 1) / DYNAKV_GRANULE * DYNAKV_GRANULE;
-        if (o < 0 || (o & (DYNAKV_GRANULE - 1)) || (o + seg) * ESZ > a.bytesB) {
-          bad = 1;
-        } else {
-          offB[q] = (uint32_t)(o * ESZ) + G::ld_byte(row);
-          limB[q] = seg * ESZ - G::ld_byte(row);
-        }
-      }
+      offB[q] = a.pos_off[n0 + row] + G::ld_byte(row);       // stays outside the buffer for padding rows
+      limB[q] = a.pos_len[n0 + row] - G::ld_byte(row);
     }
-    if (bad) atomicOr(&a.hdr->err, kErrKvCapacity);
-    const int t0 = a.order[n0];
-    const int k0 = t0 < 0 ? 0 : min(max(a.kcnt[t0], 0), a.M);
-    ksteps = (k0 * ESZ + G::KB - 1) / G::KB;
+    ksteps = (a.pos_len[n0] + G::KB - 1) / G::KB;
     Bbase = static_cast<const char*>(a.B);
     bytesB = (uint32_t)a.bytesB;
   } else {
