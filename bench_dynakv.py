@@ -30,6 +30,23 @@ KINDS = {4: "kv_gemm_kernel<spectral projection>", 5: "kv_gemm_kernel<gate logit
          6: "kv_mask_kernel (softmax + cumulative mask + threshold)", 7: "kv_gemm_kernel<reconstruction>"}
 
 
+TRAFFIC_KEYS = {4: "spectral_projection", 5: "gate_logits", 6: "kv_mask_kernel", 7: "reconstruction"}
+
+
+def recorded_traffic(kind: int):
+    """HBM-side bytes per launch of one kernel kind for kv_configs[2], as recorded from two rocprofv3
+    --pmc runs (FETCH_SIZE, WRITE_SIZE; scaling stated in the file).  None if absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_dynakv.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == TRAFFIC_KEYS[kind]:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -144,19 +161,20 @@ def main(argv=None) -> int:
         avg = ms / cnt if cnt else 0.0
         if kind == 6:
             rate = mask_bytes / (avg * 1e-3) / 1e9 if avg else 0.0
-            kinds.append({"kernel": name, "launches": int(cnt), "avg_ms": avg, "bound": "hbm", "gbs": rate,
-                          "frac": rate / PEAK_HBM_GBS})
+            kinds.append({"kernel": name, "kind": kind, "launches": int(cnt), "avg_ms": avg, "bound": "hbm",
+                          "gbs": rate, "frac": rate / PEAK_HBM_GBS})
         else:
             rate = work[kind] / (avg * 1e-3) / 1e12 if avg else 0.0
-            kinds.append({"kernel": name, "launches": int(cnt), "avg_ms": avg, "bound": "mfma", "tflops": rate,
-                          "frac": rate / peak})
+            kinds.append({"kernel": name, "kind": kind, "launches": int(cnt), "avg_ms": avg, "bound": "mfma",
+                          "tflops": rate, "frac": rate / peak})
     dom = max(kinds, key=lambda e: e["avg_ms"])
+    traffic = recorded_traffic(dom["kind"]) if args.config == 2 else None
     if dom["bound"] == "mfma":
         roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak,
-                    "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "avg_launch_ms": dom["avg_ms"]}
+                    "unit": "TFLOP/s", "frac": dom["frac"], "traffic": traffic, "avg_launch_ms": dom["avg_ms"]}
     else:
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": dom["frac"], "traffic": None, "avg_launch_ms": dom["avg_ms"]}
+                    "unit": "GB/s", "frac": dom["frac"], "traffic": traffic, "avg_launch_ms": dom["avg_ms"]}
 
     cpu = None
     if args.cpu_rows > 0:
