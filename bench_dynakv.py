@@ -106,7 +106,6 @@ def main(argv=None) -> int:
     inp = kv.kv_inputs(cfg)
     log(f"inputs done ({time.perf_counter() - t_gen:.1f} s)")
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    esz = 2 if cfg.dtype == "bf16" else 4
     x, U, W, Ui, b = (to_device(inp[key]) for key in ("x", "U", "W", "U_inv", "b"))
     desc = L.make_kv_desc(cfg.n, cfg.d, cfg.dtype)
     assert L.dynakv_validate_desc(desc) == 0
