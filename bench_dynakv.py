@@ -119,7 +119,7 @@ def main(argv=None) -> int:
 
     def step():
         L.dynakv_gate(desc, x, U, W, b, cfg.tau, xt, k, None, None, ws)
-        L.dynakv_store(desc, xt, k, off, packed, n * d, ws)
+        L.dynakv_store(desc, xt, k, 0, off, packed, n * d, ws)
         L.dynakv_reconstruct(desc, packed, n * d, off, k, Ui, xbar, ws)
 
     if args.calibrate_copy:

@@ -86,17 +86,21 @@ LMHEAD_API int dynakv_gate(const dynakv_desc* desc, const void* x, const void* U
 
 /*
  * The ragged store (the components that Eq. 2 leaves and that are "explicitly persisted").
- *     off[0] = 0,  off[i+1] = off[i] + roundup(k[i], 8)
+ *     off[0] = off_base,  off[i+1] = off[i] + roundup(k[i], 8)
  *     packed[off[i] + j] = xt[i][j]  for j < k[i],   0 for k[i] <= j < roundup(k[i], 8)
- *   xt      [n x d] storage type (in)      k  int32[n], each in [0, d]  (in)
- *   off     int64[n+1]           (out)
- *   packed  storage type, `capacity` elements (out); 16-byte aligned
+ *   xt       [n x d] storage type (in)      k  int32[n], each in [0, d]  (in)
+ *   off_base first element offset to use: 0 for a new store; to append the tokens of a decoding step
+ *            to a cache, pass the cache's current end (its off[n_prev]) with `off` pointing at that
+ *            entry of the cache's offset array and `packed` at the cache's base.  A multiple of 8, >= 0.
+ *   off      int64[n+1]           (out)
+ *   packed   storage type, `capacity` elements counted from `packed` (out); 16-byte aligned
  * A k[i] outside [0, d] is clamped into it, and a token whose segment would end beyond
  * `capacity` is not written; either sets the error word (dynakv_check -> LMHEAD_E_RANGE).
- * n * d elements always suffice.
+ * off_base + n * d elements always suffice.
  */
-LMHEAD_API int dynakv_store(const dynakv_desc* desc, const void* xt, const int32_t* k, int64_t* off,
-                            void* packed, int64_t capacity, void* ws, size_t ws_bytes, void* stream);
+LMHEAD_API int dynakv_store(const dynakv_desc* desc, const void* xt, const int32_t* k, int64_t off_base,
+                            int64_t* off, void* packed, int64_t capacity, void* ws, size_t ws_bytes,
+                            void* stream);
 
 /*
  * Dynamic low-rank reconstruction (Eq. 3): x_bar_i = x^_i[0:k_i] U^-1[0:k_i, :], a product whose

@@ -106,19 +106,20 @@ int dynakv_gate(const dynakv_desc* desc, const void* x, const void* U, const voi
   return LMHEAD_OK;
 }
 
-int dynakv_store(const dynakv_desc* desc, const void* xt, const int32_t* k, int64_t* off, void* packed,
-                 int64_t capacity, void* ws, size_t ws_bytes, void* stream) {
+int dynakv_store(const dynakv_desc* desc, const void* xt, const int32_t* k, int64_t off_base, int64_t* off,
+                 void* packed, int64_t capacity, void* ws, size_t ws_bytes, void* stream) {
   Ws w;
   const int rc = open_ws(desc, ws, ws_bytes, w);
   if (rc != LMHEAD_OK) return rc;
   if (!xt || !k || !off || !packed) return LMHEAD_E_NULL;
-  if (capacity < 0) return LMHEAD_E_SHAPE;
+  if (capacity < 0 || off_base < 0 || off_base % DYNAKV_GRANULE != 0) return LMHEAD_E_SHAPE;
   if (!aligned16(xt) || !aligned16(packed) || (reinterpret_cast<uintptr_t>(off) & 7u)) return LMHEAD_E_ALIGN;
   const KvLayout& L = w.L;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WsHeader* hdr = w.at<WsHeader>(L.hdr);
   LM_TRY(launch_kv_clear_header(hdr, s));
-  LM_TRY(launch_kv_store(desc->dtype, xt, k, L.n, desc->d, off, packed, capacity, w.at<int64_t>(L.blocksum), hdr, s));
+  LM_TRY(launch_kv_store(desc->dtype, xt, k, L.n, desc->d, off_base, off, packed, capacity,
+                         w.at<int64_t>(L.blocksum), hdr, s));
   return LMHEAD_OK;
 }
 

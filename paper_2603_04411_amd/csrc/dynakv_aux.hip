@@ -240,7 +240,8 @@ __global__ __launch_bounds__(1024) void kv_scan_blocks_kernel(int64_t* __restric
 // off[i] = prefix of the block + exclusive prefix inside the block; off[n] = grand total.
 __global__ __launch_bounds__(1024) void kv_scan_offsets_kernel(const int32_t* __restrict__ k, int64_t n, int d,
                                                                const int64_t* __restrict__ blocksum,
-                                                               int nblocks, int64_t* __restrict__ off) {
+                                                               int nblocks, int64_t off_base,
+                                                               int64_t* __restrict__ off) {
   __shared__ int buf[1024];
   const int64_t i = (int64_t)blockIdx.x * kKvScanBlock + threadIdx.x;
   int bad = 0;
@@ -253,8 +254,8 @@ __global__ __launch_bounds__(1024) void kv_scan_offsets_kernel(const int32_t* __
     buf[threadIdx.x] += y;
     __syncthreads();
   }
-  if (i < n) off[i] = blocksum[blockIdx.x] + buf[threadIdx.x] - x;
-  if (i == n - 1) off[n] = blocksum[nblocks];
+  if (i < n) off[i] = off_base + blocksum[blockIdx.x] + buf[threadIdx.x] - x;
+  if (i == n - 1) off[n] = off_base + blocksum[nblocks];
 }
 static_assert(kKvScanBlock == 1024, "the offset kernel scans one token per thread");
 
@@ -489,12 +490,14 @@ hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const 
   return hipGetLastError();
 }
 
-hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t* off,
-                           void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr, hipStream_t s) {
+hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t off_base,
+                           int64_t* off, void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr,
+                           hipStream_t s) {
   const int nblocks = (int)((n + kKvScanBlock - 1) / kKvScanBlock);
   hipLaunchKernelGGL(kv_scan_totals_kernel, dim3(nblocks), dim3(256), 0, s, k, n, d, blocksum, hdr);
   hipLaunchKernelGGL(kv_scan_blocks_kernel, dim3(1), dim3(1024), 0, s, blocksum, nblocks);
-  hipLaunchKernelGGL(kv_scan_offsets_kernel, dim3(nblocks), dim3(1024), 0, s, k, n, d, blocksum, nblocks, off);
+  hipLaunchKernelGGL(kv_scan_offsets_kernel, dim3(nblocks), dim3(1024), 0, s, k, n, d, blocksum, nblocks, off_base,
+                     off);
   const dim3 grid((unsigned)((n + 3) / 4));
   if (dtype == LMHEAD_BF16)
     hipLaunchKernelGGL(kv_pack_kernel<__bf16>, grid, dim3(256), 0, s, static_cast<const __bf16*>(xt), k, off, n, d,

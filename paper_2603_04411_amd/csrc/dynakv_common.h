@@ -86,9 +86,10 @@ hipError_t launch_kv_gemm(int dtype, const KvGemmArgs& a, hipStream_t s);
 hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const void* xt, int64_t n, int d,
                           float tau, bool literal, int32_t* k, float* m, void* xhat, hipStream_t s);
 
-// off = exclusive prefix sum of roundup(k, 8); then the segments are copied.
-hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t* off,
-                           void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr, hipStream_t s);
+// off = off_base + exclusive prefix sum of roundup(k, 8); then the segments are copied.
+hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t off_base,
+                           int64_t* off, void* packed, int64_t capacity, int64_t* blocksum, WsHeader* hdr,
+                           hipStream_t s);
 
 // order = tokens sorted by descending number of K-steps (ceil(k * esz / 128)), padded with -1 up to
 // ncap; pos_off / pos_len = byte offset and byte length (k rounded up to the granule) of each sorted

@@ -40,7 +40,7 @@ def _lib():
         lib.dynakv_gate.restype = C.c_int
         lib.dynakv_gate.argtypes = [dp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
         lib.dynakv_store.restype = C.c_int
-        lib.dynakv_store.argtypes = [dp, vp, vp, vp, vp, i64, vp, sz, vp]
+        lib.dynakv_store.argtypes = [dp, vp, vp, i64, vp, vp, i64, vp, sz, vp]
         lib.dynakv_reconstruct.restype = C.c_int
         lib.dynakv_reconstruct.argtypes = [dp, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         lib.dynakv_retain.restype = C.c_int
@@ -74,9 +74,9 @@ def dynakv_gate(desc, x, U, W, b, tau, xt, k, m, xhat, ws) -> None:
     _check(rc, "dynakv_gate")
 
 
-def dynakv_store(desc, xt, k, off, packed, capacity, ws) -> None:
-    rc = _lib().dynakv_store(C.byref(desc), _ptr(xt), _ptr(k), _ptr(off), _ptr(packed), capacity, _ptr(ws),
-                             _nbytes(ws), _stream())
+def dynakv_store(desc, xt, k, off_base, off, packed, capacity, ws) -> None:
+    rc = _lib().dynakv_store(C.byref(desc), _ptr(xt), _ptr(k), off_base, _ptr(off), _ptr(packed), capacity,
+                             _ptr(ws), _nbytes(ws), _stream())
     _check(rc, "dynakv_store")
 
 

@@ -142,13 +142,15 @@ class KvProblem:
         self.L.dynakv_gate(self.desc, self.x, self.U, self.W, self.b, tau, xt, k, m, xhat, self.ws)
         return xt, k, m, xhat
 
-    def store(self, xt, k, capacity=None):
+    def store(self, xt, k, capacity=None, off_base=0, off=None, packed=None):
         import torch
         cfg = self.cfg
-        capacity = cfg.n * cfg.d if capacity is None else capacity
-        off = torch.full((cfg.n + 1,), -1, dtype=torch.int64, device="cuda")
-        packed = torch.full((max(capacity, 8),), 5.0, dtype=self.tdt, device="cuda")
-        self.L.dynakv_store(self.desc, xt, k, off, packed, capacity, self.ws)
+        capacity = off_base + cfg.n * cfg.d if capacity is None else capacity
+        if off is None:
+            off = torch.full((cfg.n + 1,), -1, dtype=torch.int64, device="cuda")
+        if packed is None:
+            packed = torch.full((max(capacity, 8),), 5.0, dtype=self.tdt, device="cuda")
+        self.L.dynakv_store(self.desc, xt, k, off_base, off, packed, capacity, self.ws)
         return off, packed
 
     def reconstruct(self, packed, packed_elems, off, k):

@@ -249,3 +249,31 @@ def test_wide_state_uses_the_multi_pass_mask_kernel():
     xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
     assert kp.check() == 0
     assert rel_fro(np64(xbar), o["xbar"]) <= 1e-2
+
+
+def test_append_to_an_existing_store():
+    """Decoding appends: a prefill of 500 tokens is stored, then two steps of 40 and 1 tokens are
+    appended with off_base = the cache's end; offsets, packed bytes and the reconstruction of the whole
+    cache must equal those of storing all 541 tokens at once."""
+    import torch
+    cfg = kv.KV_CONFIGS[1].scaled(n=541, d=192)
+    inp = kv.kv_inputs(cfg)
+    whole = KvProblem(cfg, inp)
+    xt, k, _, _ = whole.gate(cfg.tau, soft=False)
+    off_all, packed_all = whole.store(xt, k)
+    total = int(off_all[-1].item())
+    cache_off = torch.full((cfg.n + 1,), -1, dtype=torch.int64, device="cuda")
+    cache = torch.full((cfg.n * cfg.d,), 5.0, dtype=whole.tdt, device="cuda")
+    start, end_off = 0, 0
+    for count in (500, 40, 1):
+        part = KvProblem(cfg.scaled(n=count), {**inp, "x": inp["x"][start:start + count]})
+        part.store(xt[start:start + count], k[start:start + count], capacity=cfg.n * cfg.d, off_base=end_off,
+                   off=cache_off[start:], packed=cache)
+        assert part.check() == 0
+        start += count
+        end_off = int(cache_off[start].item())
+    assert bool((cache_off == off_all).all()) and end_off == total
+    assert bool((cache[:total] == packed_all[:total]).all()) and bool((cache[total:] == 5.0).all())
+    xbar = whole.reconstruct(cache, total, cache_off, k)
+    ref = whole.reconstruct(packed_all, total, off_all, k)
+    assert whole.check() == 0 and bool((xbar == ref).all())

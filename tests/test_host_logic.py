@@ -130,9 +130,11 @@ def test_dynakv_descriptor_and_argument_validation(lib):
     assert gate(d, p, p, p, p, 0.1, p, p, None, None, p + 16, need, None) == -4
     assert gate(d, p, p, p, p, 0.1, p, p, None, None, p, need - 1, None) == -5
     assert gate(d, p, p, p, p, 0.1, p, p, None, None, None, need, None) == -1
-    assert store(d, p, p, None, p, 1 << 20, p, need, None) == -1
-    assert store(d, p, p, p, p, -1, p, need, None) == -2
-    assert store(d, p, p, p + 4, p, 1 << 20, p, need, None) == -4
+    assert store(d, p, p, 0, None, p, 1 << 20, p, need, None) == -1
+    assert store(d, p, p, 0, p, p, -1, p, need, None) == -2
+    assert store(d, p, p, 12, p, p, 1 << 20, p, need, None) == -2       # base offset not on a granule
+    assert store(d, p, p, -8, p, p, 1 << 20, p, need, None) == -2
+    assert store(d, p, p, 0, p + 4, p, 1 << 20, p, need, None) == -4
     assert rec(d, p, 1 << 20, p, p, None, p, p, need, None) == -1
     assert rec(d, p, 1 << 31, p, p, p, p, p, need, None) == -2       # more than 2^31 bytes of bf16
     assert rec(d, p, 1 << 20, p, p, p, p, p, 100, None) == -5
