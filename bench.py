@@ -3,7 +3,7 @@
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input, all
 tensors already resident in HBM:
-    lmhead_logprob_fwd(theta) [+ fwd(old), fwd(ref) where the workload recomputes them]
+    lmhead_logprob_fwd(theta) [lmhead_logprob_fwd_multi(theta, old, ref) where the workload recomputes them]
     -> group_advantage -> grpo_loss | flowrl_tb_loss -> lmhead_logprob_bwd (dH, dW).
 Prints ONE JSON line (metric: valid tokens/s of the step) with a `roofline` object for the
 dominant matrix-core kernel (timed with HIP events inside the library, on the launch stream)
@@ -102,6 +102,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the target config)")
     ap.add_argument("--vocab-chunk", type=int, default=0)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--separate-forwards", action="store_true",
+                    help="where the step recomputes old/reference log-probs, use one forward call per policy "
+                         "instead of the single multi-policy pass (for comparison)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference point for FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -138,7 +141,9 @@ def main() -> int:
 
     desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=args.vocab_chunk)
     assert L.validate_desc(desc) == 0
-    ws = torch.empty(L.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    n_pol = (3 if cfg.loss == "grpo" else 2) if cfg.recompute_old_ref else 1
+    ws = torch.empty(max(L.workspace_bytes(desc), L.multi_workspace_bytes(desc, n_pol)), dtype=torch.uint8,
+                     device="cuda")
     loss_ws = torch.empty(L.loss_workspace_bytes(cfg.P, cfg.G, cfg.T), dtype=torch.uint8, device="cuda")
     N = cfg.N
     logp, lse = torch.empty(N, **f32), torch.empty(N, **f32)
@@ -159,9 +164,16 @@ def main() -> int:
         L.lmhead_logprob_fwd(desc, H, W_ref, tok_d, lens_d, lp_ref, scratch_lse, None, None, None, ws)
 
     def step():
-        L.lmhead_logprob_fwd(desc, H, W, tok_d, lens_d, logp, lse, ent, None, None, ws)
-        if cfg.recompute_old_ref:
+        if cfg.recompute_old_ref and args.separate_forwards:
+            L.lmhead_logprob_fwd(desc, H, W, tok_d, lens_d, logp, lse, ent, None, None, ws)
             fwd_other()
+        elif cfg.recompute_old_ref:
+            # current, old and reference policy share the hidden states: one pass over all of them
+            mats = [W, W_old, W_ref] if W_old is not None else [W, W_ref]
+            outs = [logp, lp_old, lp_ref] if W_old is not None else [logp, lp_ref]
+            L.lmhead_logprob_fwd_multi(desc, H, mats, tok_d, lens_d, outs, lse, ent, None, None, ws)
+        else:
+            L.lmhead_logprob_fwd(desc, H, W, tok_d, lens_d, logp, lse, ent, None, None, ws)
         if cfg.loss == "grpo":
             L.group_advantage(rew_d, cfg.P, cfg.G, 1e-6, 0, adv)
             L.grpo_loss(logp, lp_old, lp_ref, adv, lens_d, cfg.P, cfg.G, cfg.T, cfg.clip_eps, cfg.clip_eps,

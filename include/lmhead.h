@@ -110,6 +110,24 @@ LMHEAD_API int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const 
                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same forward for several weight matrices over ONE set of hidden states, in a single pass:
+ * the indexing and the gather of the valid rows are done once and one matrix-core launch covers
+ * every (matrix, vocabulary tile) pair.  This is the step of a policy-optimisation iteration that
+ * evaluates the current, the sampling ("old") and the reference policy on the same hidden states.
+ *   W      host array of npol device pointers, each [V x d] with row stride ldW (1 <= npol <= 4)
+ *   logp   host array of npol device pointers, each float[N]                         (out)
+ *   lse, entropy   of the FIRST matrix only (NULL to skip)                            (out)
+ * Needs lmhead_multi_workspace_bytes(desc, npol) bytes of scratch (0 if the arguments are invalid);
+ * everything else as for lmhead_logprob_fwd, whose results it reproduces bit for bit.
+ */
+LMHEAD_API size_t lmhead_multi_workspace_bytes(const lmhead_desc* desc, int32_t npol);
+LMHEAD_API int lmhead_logprob_fwd_multi(const lmhead_desc* desc, const void* H, const void* const* W,
+                             int32_t npol, const int32_t* tok, const int32_t* len,
+                             float* const* logp, float* lse, float* entropy,
+                             uint8_t* mask, int32_t* cu_len,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Backward through the same chunked softmax.  Given g_logp[i] = dL/dlogp_i (0 on
  * padding) and the lse saved by the forward:
  *     dZ[i,v] = g_i (1[v == y_i] - exp(z[i,v] - lse_i))     (recomputed per vocabulary chunk)

@@ -16,6 +16,8 @@ from .binding import (
     loss_workspace_bytes,
     validate_desc,
     lmhead_logprob_fwd,
+    lmhead_logprob_fwd_multi,
+    multi_workspace_bytes,
     lmhead_logprob_bwd,
     group_advantage,
     grpo_loss,
@@ -45,6 +47,6 @@ __all__ = [
     "dynakv_store", "dynakv_reconstruct", "dynakv_retain", "dynakv_check", "DYNAKV_SYMBOLS",
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
-    "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
+    "lmhead_logprob_fwd", "lmhead_logprob_fwd_multi", "multi_workspace_bytes", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
     "flowrl_tb_loss", "ce_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
 ]

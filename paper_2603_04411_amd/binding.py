@@ -15,7 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTED_SYMBOLS = [
     "lmhead_abi_version", "lmhead_workspace_bytes", "lmhead_validate_desc",
-    "lmhead_logprob_fwd", "lmhead_logprob_bwd", "group_advantage",
+    "lmhead_logprob_fwd", "lmhead_logprob_bwd", "lmhead_multi_workspace_bytes", "lmhead_logprob_fwd_multi",
+    "group_advantage",
     "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "ce_loss", "lmhead_check",
     "lmhead_timing_enable", "lmhead_timing_read",
 ]
@@ -73,6 +74,11 @@ def load_library():
     lib.lmhead_validate_desc.argtypes = [dp]
     lib.lmhead_logprob_fwd.restype = C.c_int
     lib.lmhead_logprob_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lmhead_multi_workspace_bytes.restype = sz
+    lib.lmhead_multi_workspace_bytes.argtypes = [dp, i32]
+    lib.lmhead_logprob_fwd_multi.restype = C.c_int
+    lib.lmhead_logprob_fwd_multi.argtypes = [dp, vp, C.POINTER(vp), i32, vp, vp, C.POINTER(vp), vp, vp, vp, vp, vp,
+                                             sz, vp]
     lib.lmhead_logprob_bwd.restype = C.c_int
     lib.lmhead_logprob_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.group_advantage.restype = C.c_int
@@ -137,6 +143,23 @@ def lmhead_logprob_fwd(desc, H, W, tok, lens, logp, lse, entropy, mask, cu_len, 
         C.byref(desc), _ptr(H), _ptr(W), _ptr(tok), _ptr(lens), _ptr(logp), _ptr(lse), _ptr(entropy),
         _ptr(mask), _ptr(cu_len), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "lmhead_logprob_fwd")
+
+
+def multi_workspace_bytes(desc: LmheadDesc, npol: int) -> int:
+    return int(load_library().lmhead_multi_workspace_bytes(C.byref(desc), npol))
+
+
+def lmhead_logprob_fwd_multi(desc, H, Ws, tok, lens, logps, lse, entropy, mask, cu_len, ws) -> None:
+    """Ws / logps: sequences of npol device tensors (weight matrices / log-prob outputs)."""
+    npol = len(Ws)
+    if len(logps) != npol:
+        raise ValueError("one log-prob output per weight matrix")
+    w_arr = (C.c_void_p * npol)(*[_ptr(t) for t in Ws])
+    lp_arr = (C.c_void_p * npol)(*[_ptr(t) for t in logps])
+    rc = load_library().lmhead_logprob_fwd_multi(
+        C.byref(desc), _ptr(H), w_arr, npol, _ptr(tok), _ptr(lens), lp_arr, _ptr(lse), _ptr(entropy),
+        _ptr(mask), _ptr(cu_len), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "lmhead_logprob_fwd_multi")
 
 
 def lmhead_logprob_bwd(desc, H, W, tok, lens, lse, g_logp, dH, dW, ws) -> None:

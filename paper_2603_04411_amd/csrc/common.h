@@ -59,7 +59,12 @@ static inline int64_t default_vocab_chunk(const lmhead_desc* d) {
 }
 
 
-static inline WsLayout make_layout(const lmhead_desc* d) {
+// Weight matrices one forward launch can evaluate over the same hidden states.
+constexpr int kMaxPolicies = 4;
+
+// npol: number of weight matrices of a multi-policy forward (each has its own target-logit vector
+// and planes of per-tile softmax statistics).
+static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
   WsLayout L{};
   L.esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
   L.R = (int64_t)d->P * d->G;
@@ -85,8 +90,8 @@ static inline WsLayout make_layout(const lmhead_desc* d) {
   L.tok_c = take((size_t)L.Ncap * 4);
   L.g_c = take((size_t)L.Ncap * 4);
   L.lse_c = take((size_t)L.Ncap * 4);
-  L.zy = take((size_t)L.Ncap * 4);
-  L.part = take((size_t)3 * L.ntiles * L.Ncap * 4);
+  L.zy = take((size_t)npol * L.Ncap * 4);
+  L.part = take((size_t)npol * 3 * L.ntiles * L.Ncap * 4);
   const int64_t pad = 128 / L.esz;
   L.ldHc = d->d + pad;
   L.ldHcT = L.Ncap + pad;
@@ -109,11 +114,11 @@ hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t
                         int32_t* row_slot, uint8_t* mask_out, int32_t* cu_out, hipStream_t s);
 
 // Gathers the valid rows of H into the dense, zero-padded Hc[Ncap x d]; also compacts tok
-// (range-checked), and optionally g_logp and lse.  zy is cleared.
+// (range-checked), and optionally g_logp and lse.  The npol vectors zy[p * Ncap + .] are cleared.
 hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
                           const float* g, const float* lse, int64_t N, WsHeader* hdr,
                           const int32_t* row_slot, void* Hc, int64_t ldHc, int32_t* tok_c, float* g_c,
-                          float* lse_c, float* zy, hipStream_t s);
+                          float* lse_c, float* zy, int npol, int64_t Ncap, hipStream_t s);
 
 // out[c][r] = in[r][c] for r < rows (rows read from the header when rows_from_nv), zero padding
 // up to out's extent [cols_p x rows_p] (pitch ld_out >= rows_p).
@@ -124,15 +129,16 @@ hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t ro
 struct FwdArgs {
   const void* Hc;      // [Ncap x d], pitch ldHc
   int64_t ldHc;
-  const void* W;       // [V x d], stride ldW
+  const void* W[kMaxPolicies];   // npol matrices [V x d], stride ldW (same hidden states for all)
+  int npol;
   int64_t ldW;
   int d, V;
   int64_t Ncap;
-  int ntiles;          // vocabulary tiles (one per workgroup)
+  int ntiles;          // vocabulary tiles (one per workgroup and policy)
   const int32_t* tok_c;
   const WsHeader* hdr;
-  float* part;         // [3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
-  float* zy;           // [Ncap]
+  float* part;         // [npol][3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
+  float* zy;           // [npol][Ncap]
 };
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s);
 

@@ -62,14 +62,12 @@ size_t lmhead_workspace_bytes(const lmhead_desc* desc) {
   return make_layout(desc).total;
 }
 
-int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
-                       const int32_t* len, float* logp, float* lse, float* entropy, uint8_t* mask,
-                       int32_t* cu_len, void* ws, size_t ws_bytes, void* stream) {
-  const int rc = validate(desc);
-  if (rc != LMHEAD_OK) return rc;
-  if (!H || !W || !tok || !len || !logp || !ws) return LMHEAD_E_NULL;
-  if (!aligned16(H) || !aligned16(W) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LMHEAD_E_ALIGN;
-  Ws w{make_layout(desc), static_cast<char*>(ws)};
+// Shared body of the two forward entry points: index, compaction, one logits launch over all
+// npol weight matrices, then one merge of the per-tile statistics per matrix.
+static int forward(const lmhead_desc* desc, const void* H, const void* const* W, int npol, const int32_t* tok,
+                   const int32_t* len, float* const* logp, float* lse, float* entropy, uint8_t* mask,
+                   int32_t* cu_len, void* ws, size_t ws_bytes, void* stream) {
+  Ws w{make_layout(desc, npol), static_cast<char*>(ws)};
   if (ws_bytes < w.L.total) return LMHEAD_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WsLayout& L = w.L;
@@ -79,11 +77,12 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
                       mask, cu_len, s));
   LM_TRY(launch_compact(desc->dtype, H, desc->ldH, desc->d, desc->V, tok, nullptr, nullptr, L.N, hdr,
                         w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c), nullptr,
-                        nullptr, w.at<float>(L.zy), s));
+                        nullptr, w.at<float>(L.zy), npol, L.Ncap, s));
   FwdArgs fa{};
   fa.Hc = w.at<void>(L.Hc);
   fa.ldHc = L.ldHc;
-  fa.W = W;
+  for (int p = 0; p < kMaxPolicies; ++p) fa.W[p] = W[p < npol ? p : 0];
+  fa.npol = npol;
   fa.ldW = desc->ldW;
   fa.d = desc->d;
   fa.V = desc->V;
@@ -97,9 +96,44 @@ int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, co
     TimedLaunch tl(0, s);
     LM_TRY(launch_fwd(desc->dtype, fa, s));
   }
-  LM_TRY(launch_finalize(w.at<float>(L.part), w.at<float>(L.zy), (int)L.ntiles, L.Ncap, len,
-                         w.at<int32_t>(L.cu_len), (int)L.R, desc->T, logp, lse, entropy, s));
+  for (int p = 0; p < npol; ++p)
+    LM_TRY(launch_finalize(w.at<float>(L.part) + (size_t)p * 3 * L.ntiles * L.Ncap,
+                           w.at<float>(L.zy) + (size_t)p * L.Ncap, (int)L.ntiles, L.Ncap, len,
+                           w.at<int32_t>(L.cu_len), (int)L.R, desc->T, logp[p], p == 0 ? lse : nullptr,
+                           p == 0 ? entropy : nullptr, s));
   return LMHEAD_OK;
+}
+
+int lmhead_logprob_fwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
+                       const int32_t* len, float* logp, float* lse, float* entropy, uint8_t* mask,
+                       int32_t* cu_len, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (!H || !W || !tok || !len || !logp || !ws) return LMHEAD_E_NULL;
+  if (!aligned16(H) || !aligned16(W) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LMHEAD_E_ALIGN;
+  return forward(desc, H, &W, 1, tok, len, &logp, lse, entropy, mask, cu_len, ws, ws_bytes, stream);
+}
+
+size_t lmhead_multi_workspace_bytes(const lmhead_desc* desc, int32_t npol) {
+  if (validate(desc) != LMHEAD_OK || npol < 1 || npol > kMaxPolicies) return 0;
+  const size_t fwd = make_layout(desc, npol).total, base = make_layout(desc).total;
+  return fwd > base ? fwd : base;
+}
+
+int lmhead_logprob_fwd_multi(const lmhead_desc* desc, const void* H, const void* const* W, int32_t npol,
+                             const int32_t* tok, const int32_t* len, float* const* logp, float* lse,
+                             float* entropy, uint8_t* mask, int32_t* cu_len, void* ws, size_t ws_bytes,
+                             void* stream) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (npol < 1 || npol > kMaxPolicies) return LMHEAD_E_SHAPE;
+  if (!H || !W || !tok || !len || !logp || !ws) return LMHEAD_E_NULL;
+  for (int p = 0; p < npol; ++p) {
+    if (!W[p] || !logp[p]) return LMHEAD_E_NULL;
+    if (!aligned16(W[p])) return LMHEAD_E_ALIGN;
+  }
+  if (!aligned16(H) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LMHEAD_E_ALIGN;
+  return forward(desc, H, W, npol, tok, len, logp, lse, entropy, mask, cu_len, ws, ws_bytes, stream);
 }
 
 int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
@@ -122,7 +156,7 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
                       nullptr, nullptr, s));
   LM_TRY(launch_compact(dt, H, desc->ldH, desc->d, desc->V, tok, g_logp, lse, L.N, hdr,
                         w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c),
-                        w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), s));
+                        w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), 1, L.Ncap, s));
   // K-contiguous copies of the two operands that the backward contracts along their rows
   LM_TRY(launch_transpose(dt, w.at<void>(L.Hc), L.ldHc, L.Ncap, desc->d, true, hdr, w.at<void>(L.HcT),
                           L.ldHcT, L.Ncap, L.dp, s));

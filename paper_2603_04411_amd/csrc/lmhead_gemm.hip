@@ -57,8 +57,17 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   const int nblk = (nv + G::BN - 1) / G::BN;
   // one vocabulary tile x one token block per workgroup: short-lived workgroups are dispatched in
   // tile-walk order, which keeps the ones that share operand slabs in step with each other
-  int tile, nb;
-  if (!xcd_tile_coords(blockIdx.x, a.ntiles, nblk, kFwdMapBx, kFwdMapBy, tile, nb)) return;
+  // a launch may cover several weight matrices over the same hidden states: the walk's x axis then
+  // runs over (policy, vocabulary tile), and neighbours in x still share the token block's rows of Hc
+  int tx, nb;
+  if (!xcd_tile_coords(blockIdx.x, a.ntiles * a.npol, nblk, kFwdMapBx, kFwdMapBy, tx, nb)) return;
+  const int pol = tx / a.ntiles;
+  const int tile = tx - pol * a.ntiles;
+  const char* Wp = static_cast<const char*>(a.W[0]);
+#pragma unroll
+  for (int p = 1; p < kMaxPolicies; ++p) Wp = (pol == p) ? static_cast<const char*>(a.W[p]) : Wp;
+  float* const zy = a.zy + (size_t)pol * a.Ncap;
+  float* const part = a.part + (size_t)pol * 3 * a.ntiles * a.Ncap;
   const int64_t n0 = (int64_t)nb * G::BN;
   const int m0 = tile * G::BM;
   const int ksteps = a.d * Elem<E>::size / G::KB;
@@ -78,8 +87,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   }
   typename G::Acc acc;
   G::zero(acc);
-  G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
-                                   static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+  G::run(acc, Wp + (int64_t)m0 * pitchW, offA, static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
 
   float mr[G::TN], sr[G::TN], tr[G::TN];
 #pragma unroll
@@ -112,7 +120,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
             zsel = eq ? acc[i][j][v] : zsel;
             found |= eq;
           }
-        if (found) a.zy[n0 + G::n_of(j)] = zsel;
+        if (found) zy[n0 + G::n_of(j)] = zsel;
       }
     }
   }
@@ -184,9 +192,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
     const size_t base = (size_t)tile * a.Ncap + n0 + n;
     const size_t plane = (size_t)a.ntiles * a.Ncap;
-    a.part[base] = m;
-    a.part[plane + base] = s;
-    a.part[2 * plane + base] = t;
+    part[base] = m;
+    part[plane + base] = s;
+    part[2 * plane + base] = t;
   }
 }
 
@@ -431,7 +439,7 @@ hipError_t allow_lds(K kernel, int bytes) {
 }  // namespace
 
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s) {
-  const dim3 grid(xcd_grid_size(a.ntiles, a.Ncap / kTile, kFwdMapBy));
+  const dim3 grid(xcd_grid_size(a.ntiles * a.npol, a.Ncap / kTile, kFwdMapBy));
   hipError_t e;
   if (dtype == LMHEAD_BF16) {
     using G = Tile<bf16_tag>;

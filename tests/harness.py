@@ -45,6 +45,19 @@ class GpuProblem:
                                   logp, lse, ent, mask, cu, self.ws)
         return logp, lse, ent, mask, cu
 
+    def fwd_multi(self, Ws, want_entropy=True):
+        """One pass over several weight matrices (device tensors); returns ([logp...], lse, entropy)."""
+        import torch
+        cfg = self.cfg
+        f = dict(dtype=torch.float32, device="cuda")
+        logps = [torch.full((cfg.N,), 7.0, **f) for _ in Ws]
+        lse = torch.full((cfg.N,), 7.0, **f)
+        ent = torch.full((cfg.N,), 7.0, **f) if want_entropy else None
+        ws = torch.empty(self.L.multi_workspace_bytes(self.desc, len(Ws)), dtype=torch.uint8, device="cuda")
+        self.L.lmhead_logprob_fwd_multi(self.desc, self.H, Ws, self.tok, self.lens, logps, lse, ent, None, None, ws)
+        assert self.L.lmhead_check(ws) == 0
+        return logps, lse, ent
+
     def bwd(self, lse, g_logp, dW_init=None):
         import torch
         cfg = self.cfg

@@ -227,3 +227,22 @@ def test_objective_variants_asymmetric_clip_token_mean_per_response_logz():
     o = O.flowrl_tb_loss(np64(d_lp), np64(d_lr), np64(adv), wl.log_z(cfg), lens, cfg.P, cfg.G, cfg.T, 1.0)
     assert abs(float(loss.item()) - o[0]) <= TOL_LOSS * abs(o[0])
     assert rel_fro(np64(g), o[1]) <= 1e-3 and rel_fro(np64(gz), o[2]) <= 1e-3
+
+
+def test_multi_policy_forward_matches_separate_passes_and_the_oracle():
+    """Current, old and reference policy over the same hidden states in one pass: bit-identical to three
+    separate forward calls, and within tolerance of the oracle."""
+    cfg = wl.CONFIGS[1].scaled(P=3, G=4, T=80, d=192, V=2 * 256 + 77)
+    inp = small_inputs(cfg)
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"])
+    Ws = [gp.W, to_device(inp["W_old"]), to_device(inp["W_ref"])]
+    logps, lse, ent = gp.fwd_multi(Ws)
+    for p, key in enumerate(("W", "W_old", "W_ref")):
+        lp1, lse1, ent1, _, _ = gp.fwd(W=Ws[p])
+        assert bool((logps[p] == lp1).all())
+        if p == 0:
+            assert bool((lse == lse1).all()) and bool((ent == ent1).all())
+        o_lp, o_lse, o_ent = O.lmhead_logprob_fwd(wl.as_f64(inp["H"]), wl.as_f64(inp[key]), inp["tok"], inp["lens"], cfg.T)
+        assert np.abs(np64(logps[p]) - o_lp).max() <= TOL_LOGP
+    two, _, _ = gp.fwd_multi(Ws[:2], want_entropy=False)
+    assert bool((two[0] == logps[0]).all()) and bool((two[1] == logps[1]).all())

@@ -78,6 +78,16 @@ def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert bwd(d, p, p, p, p, None, p, p, p, p, need, None) == -1
     assert bwd(d, p, p, p, p, p, p, p + 4, p, p, need, None) == -4
     assert bwd(d, p, p, p, p, p, p, p, p, p, 0, None) == -5
+    multi = lib.lmhead_logprob_fwd_multi
+    vp3 = (C.c_void_p * 3)(p, p, p)
+    need3 = L.multi_workspace_bytes(desc, 3)
+    assert need3 > need and L.multi_workspace_bytes(desc, 1) == need
+    assert L.multi_workspace_bytes(desc, 0) == 0 and L.multi_workspace_bytes(desc, 5) == 0
+    assert multi(d, p, vp3, 5, p, p, vp3, None, None, None, None, p, need3, None) == -2
+    assert multi(d, p, vp3, 3, p, p, vp3, None, None, None, None, p, need, None) == -5
+    assert multi(d, p, (C.c_void_p * 3)(p, None, p), 3, p, p, vp3, None, None, None, None, p, need3, None) == -1
+    assert multi(d, p, (C.c_void_p * 3)(p, p + 8, p), 3, p, p, vp3, None, None, None, None, p, need3, None) == -4
+    assert multi(d, p, vp3, 3, p, p, None, None, None, None, None, p, need3, None) == -1
     bad = L.make_desc(2, 4, 32, 100, 4096, "bf16")
     assert fwd(C.byref(bad), p, p, p, p, p, p, None, None, None, p, 1 << 40, None) == -2
     assert lib.group_advantage(None, 2, 4, 1e-6, 0, p, None) == -1
