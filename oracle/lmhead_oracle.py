@@ -67,6 +67,23 @@ def logits(H, W):
     return np.asarray(H, dtype=np.float64) @ np.asarray(W, dtype=np.float64).T
 
 
+def quantize_e4m3(x, exp2: int):
+    """The value that the 8-bit variant of the logits path sees for x: ``x * 2^exp2`` clamped to
+    [-448, 448] and rounded to the nearest OCP e4m3 number (4 exponent bits, bias 7, 3 mantissa bits,
+    subnormals down to 2^-9, ties to even), then scaled back by ``2^-exp2``.  Returns fp64.
+
+    (This variant is the benchmark's, not the paper's: parity unpinned for the paper.  The rounding
+    itself is pinned against an independent implementation in the tests.)
+    """
+    y = np.clip(np.asarray(x, dtype=np.float64) * 2.0 ** exp2, -448.0, 448.0)
+    a = np.abs(y)
+    # spacing of the e4m3 grid around |y|: 2^(floor(log2|y|) - 3), and 2^-9 in the subnormal range
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -6)))
+    step = 2.0 ** (e - 3)
+    q = np.rint(a / step) * step          # numpy rounds halves to even, as the format requires
+    return np.sign(y) * q * 2.0 ** -exp2
+
+
 def logprob_rows(H_rows, W, tok_rows):
     """Log-softmax statistics of given rows, all treated as valid.
 
@@ -305,8 +322,12 @@ def flowrl_tb_loss(logp, logp_ref, reward, logZ, lens, P, G, T, beta: float):
 # backward through the softmax (softmax Jacobian; CE special case is Eq. 9's L_CE)
 # ---------------------------------------------------------------------------
 
-def bwd_rows(H_rows, W, tok_rows, g_rows):
+def bwd_rows(H_rows, W, tok_rows, g_rows, H_logits=None, W_logits=None):
     """Gradients of sum_i g_i * logp_i for the given rows (all treated as valid).
+
+    ``H_logits`` / ``W_logits`` (default: H_rows / W) are the operands that the logits are formed
+    from; the 8-bit variant passes the e4m3-rounded copies there while the two contractions below
+    use the full-precision operands.
 
     ``d logp_i / d z_{i,v} = 1[v == y_i] - softmax(z_i)_v`` so
     ``dZ[i,v] = g_i (1[v == y_i] - exp(z_{i,v} - lse_i))``,
@@ -316,7 +337,7 @@ def bwd_rows(H_rows, W, tok_rows, g_rows):
     """
     H64 = np.asarray(H_rows, dtype=np.float64)
     W64 = np.asarray(W, dtype=np.float64)
-    z = H64 @ W64.T
+    z = logits(H64 if H_logits is None else H_logits, W64 if W_logits is None else W_logits)
     n = z.shape[0]
     M = z.max(axis=1)
     lse = M + np.log(np.exp(z - M[:, None]).sum(axis=1))
@@ -326,7 +347,7 @@ def bwd_rows(H_rows, W, tok_rows, g_rows):
     return dZ @ W64, dZ.T @ H64
 
 
-def lmhead_logprob_bwd(H, W, tok, lens, T: int, g_logp, block: int = 256):
+def lmhead_logprob_bwd(H, W, tok, lens, T: int, g_logp, block: int = 256, H_logits=None, W_logits=None):
     """dH (fp64[N,d], zero on padded rows) and dW (fp64[V,d]) for upstream g_logp[N]."""
     _, _, row_slot, _ = index_build(lens, T)
     H = np.asarray(H)
@@ -338,7 +359,8 @@ def lmhead_logprob_bwd(H, W, tok, lens, T: int, g_logp, block: int = 256):
     dW = np.zeros((V, d))
     for b0 in range(0, row_slot.size, block):
         rows = row_slot[b0:b0 + block]
-        dh, dw = bwd_rows(H[rows], W, tok[rows], g_logp[rows])
+        dh, dw = bwd_rows(H[rows], W, tok[rows], g_logp[rows],
+                          None if H_logits is None else np.asarray(H_logits)[rows], W_logits)
         dH[rows] = dh
         dW += dw
     return dH, dW

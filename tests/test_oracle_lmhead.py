@@ -187,3 +187,44 @@ def test_ce_loss_matches_library():
     ref = torch.nn.functional.cross_entropy(z, target, ignore_index=-100, reduction="mean").item()
     assert abs(loss - ref) < 1e-12
     assert np.allclose(g[mask == 1], -1.0 / lens.sum()) and np.all(g[mask == 0] == 0)
+
+
+def test_e4m3_rounding_matches_torch_and_the_format():
+    import torch
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-4, 3, 20000),
+                        [0.0, 1.0, 1.0625, 1.1875, 448.0, 464.0, 2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9, -0.3, 17.0, 19.0]])
+    x = x[np.abs(x) < 464]                                          # beyond that the raw conversion gives NaN
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = O.quantize_e4m3(x.astype(np.float32), 0)
+    assert np.array_equal(got, want)
+    # every result is on the grid: 3 mantissa bits, exponent in [-6, 8], subnormal step 2^-9
+    nz = got[got != 0]
+    m, e = np.frexp(np.abs(nz))
+    assert np.all((m * 16) % 1 == 0) or np.all(np.abs(nz) < 2.0 ** -6)
+    assert np.abs(got).max() <= 448
+    # saturation and scaling by a power of two (exact): q(x, e) = q(x * 2^e, 0) / 2^e
+    assert O.quantize_e4m3(1e9, 0) == 448 and O.quantize_e4m3(-500.0, 0) == -448
+    w = rng.standard_normal(1000) * 0.02
+    assert np.array_equal(O.quantize_e4m3(w, 12), O.quantize_e4m3(w * 4096, 0) / 4096)
+    # relative error of a normal number is at most 2^-4
+    big = w[np.abs(w) * 4096 >= 2.0 ** -6]
+    assert np.all(np.abs(O.quantize_e4m3(big, 12) - big) <= np.abs(big) * 2.0 ** -4)
+
+
+def test_backward_with_separate_logit_operands():
+    # the 8-bit variant: logits from rounded copies, contractions with the originals; with identical
+    # copies it is the ordinary backward, and dZ only depends on the logit operands
+    rng = np.random.default_rng(4)
+    H, W = rng.standard_normal((6, 8)), rng.standard_normal((11, 8))
+    tok, g = rng.integers(0, 11, 6), rng.standard_normal(6)
+    a = O.bwd_rows(H, W, tok, g)
+    b = O.bwd_rows(H, W, tok, g, H.copy(), W.copy())
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    Hq, Wq = O.quantize_e4m3(H, 5), O.quantize_e4m3(W, 5)
+    dH, dW = O.bwd_rows(H, W, tok, g, Hq, Wq)
+    z = Hq @ Wq.T
+    p = np.exp(z) / np.exp(z).sum(1, keepdims=True)
+    dZ = -p * g[:, None]
+    dZ[np.arange(6), tok] += g
+    assert np.allclose(dH, dZ @ W, atol=1e-13) and np.allclose(dW, dZ.T @ H, atol=1e-13)
