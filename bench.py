@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 KERNEL_NAMES = ["fwd_kernel (logits + online softmax)", "dz_kernel (logits recompute -> dZ)",
                 "gemm_t_kernel<dH>", "gemm_t_kernel<dW>"]
 
@@ -105,6 +106,9 @@ def main() -> int:
     ap.add_argument("--separate-forwards", action="store_true",
                     help="where the step recomputes old/reference log-probs, use one forward call per policy "
                          "instead of the single multi-policy pass (for comparison)")
+    ap.add_argument("--fp8-logits", action="store_true",
+                    help="variant: logits (forward and recompute) from e4m3 copies of H and W; NOT the headline "
+                         "configuration (it changes the numerics), reported for comparison")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference point for FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -139,7 +143,14 @@ def main() -> int:
     rew_d, logZ_d = to_device(rewards), to_device(logZ)
     nv = int(lens.sum())
 
-    desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=args.vocab_chunk)
+    fp8 = {}
+    if args.fp8_logits:
+        # power-of-two scales that bring the largest magnitude of each operand just inside the e4m3 range
+        amax_h = float(np.abs(wl.as_f64(H_host[: 1 << 16])).max())
+        amax_w = max(float(np.abs(wl.as_f64(m[: 1 << 16])).max()) for m in (W_host,))
+        fp8 = dict(flags=4, fp8_exp_h=int(np.floor(np.log2(448.0 / amax_h))) - 1,
+                   fp8_exp_w=int(np.floor(np.log2(448.0 / amax_w))) - 1)
+    desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=args.vocab_chunk, **fp8)
     assert L.validate_desc(desc) == 0
     n_pol = (3 if cfg.loss == "grpo" else 2) if cfg.recompute_old_ref else 1
     ws = torch.empty(max(L.workspace_bytes(desc), L.multi_workspace_bytes(desc, n_pol)), dtype=torch.uint8,
@@ -222,16 +233,19 @@ def main() -> int:
     for k, (ms, n) in enumerate(kern):
         passes = args.steps * (n_fwd_passes if k == 0 else 1)
         tf = flops_per_pass * passes / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        kpeak = PEAK_FP8_TFLOPS if (args.fp8_logits and k < 2) else peak     # the two logits kernels run in e4m3
         kinds.append({"kernel": KERNEL_NAMES[k], "launches": int(n), "avg_ms": ms / n if n else 0.0,
-                      "total_ms": ms, "tflops": tf, "frac": tf / peak})
+                      "total_ms": ms, "tflops": tf, "peak": kpeak, "frac": tf / kpeak})
     dom = max(range(4), key=lambda k: kern[k][0])
     dms, dn = kern[dom]
     dom_passes = args.steps * (n_fwd_passes if dom == 0 else 1)
     flops_per_launch = flops_per_pass * dom_passes / dn
     achieved = flops_per_launch / (dms / dn * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom], "achieved": achieved, "peak": peak,
-                "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": recorded_traffic(dom) if (cfg.index == 2 and not args.vocab_chunk) else None,
+    dpeak = kinds[dom]["peak"]
+    roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom], "achieved": achieved, "peak": dpeak,
+                "unit": "TFLOP/s", "frac": achieved / dpeak,
+                "traffic": recorded_traffic(dom) if (cfg.index == 2 and not args.vocab_chunk and not args.fp8_logits)
+                else None,
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": dms / dn}
     step_flops_hw = flops_per_pass * (3 + n_fwd_passes)       # executed, including the dZ recompute
     step_flops_model = flops_per_pass * 3                      # logits + dH + dW
@@ -240,7 +254,7 @@ def main() -> int:
     cpu = None
     if args.cpu_rows > 0:
         log(f"timing the oracle on {args.cpu_rows} rows")
-        cpu = cpu_baseline(cfg, H_host, W_host, tok, lens, args.cpu_rows, gpu_logp)
+        cpu = cpu_baseline(cfg, H_host, W_host, tok, lens, args.cpu_rows, None if args.fp8_logits else gpu_logp)
 
     out = {
         "metric": "tokens/s fused LM-head logprob+loss fwd+bwd (1 GPU)",
@@ -248,7 +262,7 @@ def main() -> int:
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
+        "dtype": cfg.dtype + ("+e4m3 logits" if args.fp8_logits else ""), "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}", "P": cfg.P, "G": cfg.G, "T": cfg.T,
                    "d": cfg.d, "V": cfg.V, "token_slots": cfg.N, "valid_tokens": nv, "loss": cfg.loss,
                    "vocab_chunk": int(args.vocab_chunk) or "library default",

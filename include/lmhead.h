@@ -51,7 +51,7 @@ extern "C" {
 enum {
   LMHEAD_OK = 0,
   LMHEAD_E_NULL = -1,      /* a required pointer is NULL                              */
-  LMHEAD_E_SHAPE = -2,     /* P,G,T,d,V <= 0; ld < d; d not a multiple of 64; N overflows int32 */
+  LMHEAD_E_SHAPE = -2,     /* P,G,T,d,V <= 0; ld < d; d not a multiple of 64 (128 with 8-bit logits); N overflows int32; bad exponent */
   LMHEAD_E_DTYPE = -3,     /* dtype not LMHEAD_F32 / LMHEAD_BF16, or unknown flag bits  */
   LMHEAD_E_ALIGN = -4,     /* a matrix pointer is not 16-byte aligned, or ld*elem % 16  */
   LMHEAD_E_WORKSPACE = -5, /* ws_bytes smaller than lmhead_workspace_bytes()           */
@@ -62,7 +62,12 @@ enum {
 enum { LMHEAD_F32 = 0, LMHEAD_BF16 = 1 };
 
 enum {
-  LMHEAD_FLAG_ACCUM_DW = 1u << 1 /* lmhead_logprob_bwd adds into dW instead of overwriting it */
+  LMHEAD_FLAG_ACCUM_DW = 1u << 1,   /* lmhead_logprob_bwd adds into dW instead of overwriting it */
+  LMHEAD_FLAG_FP8_LOGITS = 1u << 2  /* logits (forward and the backward's recompute) from 8-bit copies */
+                                    /* of H and W: OCP e4m3, x * 2^fp8_exp rounded to nearest even and  */
+                                    /* clamped to +-448, fp32 accumulation; dH and dW still contract    */
+                                    /* with H and W as given.  Needs d % 128 == 0.  Not the default:    */
+                                    /* it changes the logits by up to ~6 % of their spread.             */
 };
 
 /* Problem descriptor (host memory). */
@@ -73,10 +78,11 @@ typedef struct lmhead_desc {
   int32_t vocab_chunk; /* vocabulary chunk of the backward (columns of dZ held at once);  */
                        /* 0 = library default (as wide as ~48 GB of scratch allows, at    */
                        /* most 32768).  Rounded up to a multiple of the 256-wide tile.    */
-  int32_t reserved;    /* must be 0                                                        */
+  int32_t fp8_exp_h;   /* with LMHEAD_FLAG_FP8_LOGITS: H is scaled by 2^fp8_exp_h before rounding  */
+                       /* (choose it so that max|H| * 2^e <= 448); otherwise must be 0            */
   int64_t ldH, ldW;    /* row strides of H and W in elements (>= d)                       */
   uint32_t flags;      /* LMHEAD_FLAG_*                                                    */
-  uint32_t reserved2;  /* must be 0                                                        */
+  int32_t fp8_exp_w;   /* likewise for W (every W of a multi-policy forward)                       */
 } lmhead_desc;
 
 /* Scratch bytes that lmhead_logprob_fwd / lmhead_logprob_bwd need for this descriptor

@@ -29,6 +29,7 @@ ERRORS = {
 LMHEAD_F32 = 0
 LMHEAD_BF16 = 1
 FLAG_ACCUM_DW = 1 << 1
+FLAG_FP8_LOGITS = 1 << 2
 
 
 class LmheadError(RuntimeError):
@@ -41,9 +42,9 @@ class LmheadDesc(C.Structure):
     _fields_ = [
         ("P", C.c_int32), ("G", C.c_int32), ("T", C.c_int32),
         ("d", C.c_int32), ("V", C.c_int32),
-        ("dtype", C.c_int32), ("vocab_chunk", C.c_int32), ("reserved", C.c_int32),
+        ("dtype", C.c_int32), ("vocab_chunk", C.c_int32), ("fp8_exp_h", C.c_int32),
         ("ldH", C.c_int64), ("ldW", C.c_int64),
-        ("flags", C.c_uint32), ("reserved2", C.c_uint32),
+        ("flags", C.c_uint32), ("fp8_exp_w", C.c_int32),
     ]
 
 
@@ -101,11 +102,12 @@ def load_library():
     return lib
 
 
-def make_desc(P, G, T, d, V, dtype, vocab_chunk=0, ldH=None, ldW=None, flags=0) -> LmheadDesc:
+def make_desc(P, G, T, d, V, dtype, vocab_chunk=0, ldH=None, ldW=None, flags=0, fp8_exp_h=0,
+              fp8_exp_w=0) -> LmheadDesc:
     code = {"bf16": LMHEAD_BF16, "f32": LMHEAD_F32}.get(dtype, dtype)
-    return LmheadDesc(P=P, G=G, T=T, d=d, V=V, dtype=code, vocab_chunk=vocab_chunk, reserved=0,
+    return LmheadDesc(P=P, G=G, T=T, d=d, V=V, dtype=code, vocab_chunk=vocab_chunk, fp8_exp_h=fp8_exp_h,
                       ldH=d if ldH is None else ldH, ldW=d if ldW is None else ldW,
-                      flags=flags, reserved2=0)
+                      flags=flags, fp8_exp_w=fp8_exp_w)
 
 
 def workspace_bytes(desc: LmheadDesc) -> int:

@@ -13,6 +13,10 @@ namespace lmhead {
 // Macro-tile of every contraction: 256 x 256 outputs.
 constexpr int kTile = 256;
 
+// Internal operand-type code of the logits kernels when LMHEAD_FLAG_FP8_LOGITS is set (the public
+// dtype codes are LMHEAD_F32 = 0 and LMHEAD_BF16 = 1).
+constexpr int kDtypeFp8 = 2;
+
 // Sticky error bits written by kernels into WsHeader::err.
 constexpr int kErrLen = 1;  // a length outside [0, T]
 constexpr int kErrTok = 2;  // a token id outside [0, V) on a valid slot
@@ -42,7 +46,8 @@ struct WsLayout {
   // 128-byte line: a power-of-two pitch would put every row of a tile on the same L2
   // channel and set (the token-major operands have a pitch of Ncap elements, often 2^k).
   int64_t ldHc, ldHcT, ldWT, ldZ, ldZT;
-  size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, total;
+  int64_t ld8;      // pitch (bytes) of the e4m3 operand copies: d + one 128-byte line
+  size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, Hc8, W8, total;
 };
 
 // Default backward chunk: as wide as keeps the two dZ copies (worst case: every slot valid)
@@ -103,6 +108,10 @@ static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
   L.WT = take((size_t)L.dp * L.ldWT * L.esz);
   L.dZ = take((size_t)L.Ncap * L.ldZ * L.esz);
   L.dZT = take((size_t)L.Vc * L.ldZT * L.esz);
+  L.ld8 = d->d + 128;
+  const bool fp8 = (d->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
+  L.Hc8 = take(fp8 ? (size_t)L.Ncap * L.ld8 : 0);
+  L.W8 = take(fp8 ? (size_t)npol * L.Vp * L.ld8 : 0);
   L.total = off;
   return L;
 }
@@ -139,6 +148,7 @@ struct FwdArgs {
   const WsHeader* hdr;
   float* part;         // [npol][3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
   float* zy;           // [npol][Ncap]
+  float zscale;        // logits = accumulator * zscale (1, or 2^-(e_H + e_W) for e4m3 operands)
 };
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s);
 
@@ -164,8 +174,18 @@ struct DzArgs {
   const WsHeader* hdr;
   void* dZ;       // [Ncap x chunk], pitch ldZ
   void* dZT;      // [chunk x Ncap], pitch ldZT
+  float zscale;   // as in FwdArgs
 };
-hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s);
+// op_dtype: type of Hc / W as given in the arguments (LMHEAD_F32, LMHEAD_BF16 or kDtypeFp8);
+// out_dtype: type of dZ / dZT (LMHEAD_F32 or LMHEAD_BF16; equal to op_dtype unless that is e4m3).
+hipError_t launch_dz(int op_dtype, int out_dtype, const DzArgs& a, hipStream_t s);
+
+// out[r][c] = e4m3(in[r][c] * 2^exp2) (clamped to +-448, round to nearest even) for r < rows, 0 for the
+// padding rows up to rows_p; rows = header.nv when rows_from_nv (then only rows below the next tile
+// multiple are written).  cols is a multiple of 8; ld_out in bytes.
+hipError_t launch_quantize_e4m3(int dtype, const void* in, int64_t ld_in, int64_t rows_fixed, bool rows_from_nv,
+                                const WsHeader* hdr, int cols, int exp2, void* out, int64_t ld_out, int64_t rows_p,
+                                hipStream_t s);
 
 // Generic C^T-store contraction: for m < M, n < Nn: out[rowmap(n)][m] (+)= sum_k A[m][k] B[n][k].
 struct GemmTArgs {

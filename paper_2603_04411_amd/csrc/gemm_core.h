@@ -32,6 +32,10 @@
 // barrier falls before the last sub-step: its MFMAs overlap the first fragment reads of
 // the next stage and the issue of the next loads.
 //
+// 8-bit (e4m3) operands use v_mfma_f32_32x32x64_f8f6f4: a K-step is then 128 values of K, consumed
+// in two sub-steps of two chunks per lane; run_rows() has a second loop body for that case with the
+// same ring and the same four-region rhythm.
+//
 // Accumulator layout of a 32x32 block (16 floats per lane):
 //   element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4,  n = l % 32.
 #pragma once
@@ -50,8 +54,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
+typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+
 struct bf16_tag {};
 struct f32_tag {};
+struct fp8_tag {};   // OCP e4m3 operands (logits only), fp32 accumulation
 
 template <typename E>
 struct Elem;
@@ -59,23 +66,42 @@ template <>
 struct Elem<bf16_tag> {
   static constexpr int size = 2;
   static constexpr int dtype = 1;
-  __device__ static inline void mma(f32x16_t& c, const u32x4_t& a, const u32x4_t& b) {
-    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  static constexpr int frag_chunks = 1;   // 16-byte chunks of K per lane and MFMA group
+  static constexpr int mfma_per_block = 1;
+  __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[1], const u32x4_t (&b)[1]) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[0]),
+                                                __builtin_bit_cast(bf16x8_t, b[0]), c, 0, 0, 0);
   }
 };
 template <>
 struct Elem<f32_tag> {
   static constexpr int size = 4;
   static constexpr int dtype = 0;
-  __device__ static inline void mma(f32x16_t& c, const u32x4_t& a, const u32x4_t& b) {
+  static constexpr int frag_chunks = 1;
+  static constexpr int mfma_per_block = 4;
+  __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[1], const u32x4_t (&b)[1]) {
     // whole-vector casts, then named components: element-wise bit casts of a[q] are avoided
-    const f32x4_t fa = __builtin_bit_cast(f32x4_t, a);
-    const f32x4_t fb = __builtin_bit_cast(f32x4_t, b);
+    const f32x4_t fa = __builtin_bit_cast(f32x4_t, a[0]);
+    const f32x4_t fb = __builtin_bit_cast(f32x4_t, b[0]);
     c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, c, 0, 0, 0);
     c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, c, 0, 0, 0);
     c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, c, 0, 0, 0);
     c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, c, 0, 0, 0);
+  }
+};
+
+template <>
+struct Elem<fp8_tag> {
+  static constexpr int size = 1;
+  static constexpr int frag_chunks = 2;   // 32 bytes = 32 e4m3 values of K per lane
+  static constexpr int mfma_per_block = 1;
+  // v_mfma_f32_32x32x64_f8f6f4 with both formats e4m3 and no block scaling: lane l supplies row
+  // l % 32 and the 32 consecutive K values (l / 32) * 32 ... of a 64-wide K block (checked on
+  // gfx950 against an integer reference); the accumulator layout is that of the other 32x32 forms.
+  __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[2], const u32x4_t (&b)[2]) {
+    const i32x8_t va = {(int)a[0].x, (int)a[0].y, (int)a[0].z, (int)a[0].w, (int)a[1].x, (int)a[1].y, (int)a[1].z, (int)a[1].w};
+    const i32x8_t vb = {(int)b[0].x, (int)b[0].y, (int)b[0].z, (int)b[0].w, (int)b[1].x, (int)b[1].y, (int)b[1].z, (int)b[1].w};
+    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, c, 0, 0, 0, 0, 0, 0);
   }
 };
 
@@ -105,7 +131,8 @@ struct GemmTile {
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int KB = 128;                      // bytes of K per row per step (a cache line)
-  static constexpr int NSUB = KB / 32;                // K sub-steps (one fragment pair each)
+  static constexpr int FC = Elem<E>::frag_chunks;     // 16-byte chunks per lane and fragment
+  static constexpr int NSUB = KB / 32 / FC;           // K sub-steps (one fragment pair each)
   static constexpr int NSLOT = 5;                     // ring of operand-tile slots
   static constexpr int SLOT = (BM > BN ? BM : BN) * KB;
   static constexpr int LDS_BYTES = NSLOT * SLOT;
@@ -213,31 +240,46 @@ struct GemmTile {
       }
     };
 
-    u32x4_t fa[2][TM], fb[2][TN];
-    auto read_frags = [&](const char* sa, const char* sb, int s, int buf) {
-      const int ch = 2 * s + half;
+    u32x4_t fa[2][TM][FC], fb[2][TN][FC];
+    auto read_a = [&](const char* sa, int s, int buf) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int r = rA0 + i * 32;
-        fa[buf][i] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + ((ch ^ swz(r)) << 4));
+#pragma unroll
+        for (int c = 0; c < FC; ++c) {
+          const int ch = (2 * s + half) * FC + c;
+          fa[buf][i][c] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + ((ch ^ swz(r)) << 4));
+        }
       }
+    };
+    auto read_b = [&](const char* sb, int s, int buf) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int r = rB0 + j * 32;
-        fb[buf][j] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + ((ch ^ swz(r)) << 4));
+#pragma unroll
+        for (int c = 0; c < FC; ++c) {
+          const int ch = (2 * s + half) * FC + c;
+          fb[buf][j][c] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + ((ch ^ swz(r)) << 4));
+        }
       }
     };
-    auto mma_all = [&](int buf) {
+    auto read_frags = [&](const char* sa, const char* sb, int s, int buf) {
+      read_a(sa, s, buf);
+      read_b(sb, s, buf);
+    };
+    // MFMAs of the row blocks [i0, i1) of the wave tile
+    auto mma_rows = [&](int buf, int i0, int i1) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = i0; i < i1; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) Elem<E>::mma(acc[i][j], fa[buf][i], fb[buf][j]);
     };
+    auto mma_all = [&](int buf) { mma_rows(buf, 0, TM); };
 
     // Scheduling hints: behind each MFMA of a region one fragment read, and behind every
     // (MMAS / loads)-th MFMA one global->LDS load, so that nothing leaves the matrix pipe idle.
     constexpr int kDsRead = 0x100, kVmem = 0x010, kMfma = 0x008;
-    constexpr int MMAS = TM * TN * (Elem<E>::size == 2 ? 1 : 4);
+    constexpr int MMAS = TM * TN * Elem<E>::mfma_per_block;
     constexpr int FR = TM + TN;
     constexpr int LD_REGION = A_LD / NPART;     // loads per region (A_LD == B_LD is not required
     constexpr int LD_REGION_B = B_LD / NPART;   // but both are spread the same way)
@@ -277,84 +319,182 @@ struct GemmTile {
     };
 
     if (ksteps <= 0) return;
-    // ring state: slots of X(ks) and Y(ks); unit u lives in slot u % NSLOT
-    int sA = 0, sB = 1;
-    issue_x(0, 0, 0); issue_x(0, 0, 1);
-    issue_y(0, 1, 0); issue_y(0, 1, 1);
-    if (ksteps > 1) { issue_x(1, 2, 0); issue_x(1, 2, 1); }
-    if (ksteps > 1)
-      __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
-    else
-      __builtin_amdgcn_s_waitcnt(kWaitVm0);
-    __builtin_amdgcn_s_barrier();
-    frags_xy(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    int ks = 0;
-    // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) are resident or in flight; the
-    // slots of X(ks-1) and Y(ks-1) are free (all waves passed the barrier after reading them).
-    for (; ks + 2 < ksteps; ++ks) {
-      const char* ca = lds + sA * SLOT;
-      const char* cb = lds + sB * SLOT;
-      const int sB1 = next_slot(sB, 2);   // slot of Y(ks+1) == slot of X(ks-1)
-      const int sA1 = next_slot(sA, 2);   // slot of X(ks+1)
-      const int sA2 = next_slot(sA1, 2);  // slot of X(ks+2) == slot of Y(ks-1)
-      // sub-step 0 and 1: first and second half of Y(ks+1)
-      frags_xy(ca, cb, 1, 1);
-      issue_y(ks + 1, sB1, 0);
-      mma_all(0);
-      sched_region(LD_REGION_B);
-      frags_xy(ca, cb, 2, 0);
-      issue_y(ks + 1, sB1, 1);
-      mma_all(1);
-      sched_region(LD_REGION_B);
-      // sub-step 2: first half of X(ks+2)
-      frags_xy(ca, cb, 3, 1);
-      issue_x(ks + 2, sA2, 0);
-      mma_all(0);
-      sched_region(LD_REGION);
-      // hand-over: everything but the youngest A_LD/2 loads of this wave has landed
-      __builtin_amdgcn_s_waitcnt(wait_vm(A_LD / NPART));
-      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of X(ks+2);
-      // its target slot was freed by the barrier that ended K-step ks-1, not by this one
-      frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
-      issue_x(ks + 2, sA2, 1);
-      mma_all(1);
-      sched_region(LD_REGION);
-      sA = sA1;
-      sB = sB1;
-    }
-    // drain: the last two K-steps
-    for (; ks < ksteps; ++ks) {
-      const char* ca = lds + sA * SLOT;
-      const char* cb = lds + sB * SLOT;
-      const int sB1 = next_slot(sB, 2);
-      const int sA1 = next_slot(sA, 2);
-      const bool more = ks + 1 < ksteps;
-      frags_xy(ca, cb, 1, 1);
-      if (more) issue_y(ks + 1, sB1, 0);
-      mma_all(0);
-      __builtin_amdgcn_sched_barrier(0);
-      frags_xy(ca, cb, 2, 0);
-      if (more) issue_y(ks + 1, sB1, 1);
-      mma_all(1);
-      __builtin_amdgcn_sched_barrier(0);
-      frags_xy(ca, cb, 3, 1);
-      mma_all(0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (more) {
+    if constexpr (NSUB == 4) {
+      // ring state: slots of X(ks) and Y(ks); unit u lives in slot u % NSLOT
+      int sA = 0, sB = 1;
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
+      if (ksteps > 1) { issue_x(1, 2, 0); issue_x(1, 2, 1); }
+      if (ksteps > 1)
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
+      else
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      __builtin_amdgcn_s_barrier();
+      frags_xy(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      int ks = 0;
+      // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) are resident or in flight; the
+      // slots of X(ks-1) and Y(ks-1) are free (all waves passed the barrier after reading them).
+      for (; ks + 2 < ksteps; ++ks) {
+        const char* ca = lds + sA * SLOT;
+        const char* cb = lds + sB * SLOT;
+        const int sB1 = next_slot(sB, 2);   // slot of Y(ks+1) == slot of X(ks-1)
+        const int sA1 = next_slot(sA, 2);   // slot of X(ks+1)
+        const int sA2 = next_slot(sA1, 2);  // slot of X(ks+2) == slot of Y(ks-1)
+        // sub-step 0 and 1: first and second half of Y(ks+1)
+        frags_xy(ca, cb, 1, 1);
+        issue_y(ks + 1, sB1, 0);
+        mma_all(0);
+        sched_region(LD_REGION_B);
+        frags_xy(ca, cb, 2, 0);
+        issue_y(ks + 1, sB1, 1);
+        mma_all(1);
+        sched_region(LD_REGION_B);
+        // sub-step 2: first half of X(ks+2)
+        frags_xy(ca, cb, 3, 1);
+        issue_x(ks + 2, sA2, 0);
+        mma_all(0);
+        sched_region(LD_REGION);
+        // hand-over: everything but the youngest A_LD/2 loads of this wave has landed
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD / NPART));
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
+        // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of X(ks+2);
+        // its target slot was freed by the barrier that ended K-step ks-1, not by this one
         frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+        issue_x(ks + 2, sA2, 1);
+        mma_all(1);
+        sched_region(LD_REGION);
+        sA = sA1;
+        sB = sB1;
       }
-      mma_all(1);
+      // drain: the last two K-steps
+      for (; ks < ksteps; ++ks) {
+        const char* ca = lds + sA * SLOT;
+        const char* cb = lds + sB * SLOT;
+        const int sB1 = next_slot(sB, 2);
+        const int sA1 = next_slot(sA, 2);
+        const bool more = ks + 1 < ksteps;
+        frags_xy(ca, cb, 1, 1);
+        if (more) issue_y(ks + 1, sB1, 0);
+        mma_all(0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags_xy(ca, cb, 2, 0);
+        if (more) issue_y(ks + 1, sB1, 1);
+        mma_all(1);
+        __builtin_amdgcn_sched_barrier(0);
+        frags_xy(ca, cb, 3, 1);
+        mma_all(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
+          __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+        }
+        mma_all(1);
+        __builtin_amdgcn_sched_barrier(0);
+        sA = sA1;
+        sB = sB1;
+      }
+    } else {
+      // Two sub-steps per K-step (8-bit operands: an MFMA consumes 64 values of K, a sub-step two
+      // 16-byte chunks per lane and operand).  Same ring, shifted by a quarter step so that the
+      // work still falls into four equal regions of TM*TN/2 MFMAs, eight fragment reads and half a
+      // tile of loads each: the hand-over barrier sits in the middle of the K-step; after it a wave
+      // reads the first fragments of K-step ks+1 and issues Y(ks+2) into the slot of X(ks), which that
+      // barrier has just freed; X(ks+2) follows in the first half of K-step ks+1.
+      static_assert(NSUB == 2 && TM % 2 == 0, "two regions per sub-step");
+      auto read_x = [&](const char* cx, int sub, int buf) {
+        if constexpr (kLeadB) read_b(cx, sub, buf); else read_a(cx, sub, buf);
+      };
+      auto read_y = [&](const char* cy, int sub, int buf) {
+        if constexpr (kLeadB) read_a(cy, sub, buf); else read_b(cy, sub, buf);
+      };
+      constexpr int RMMAS = TM * TN / 2;     // MFMAs per region
+      constexpr int RREADS = TM * FC;        // fragment reads per region (TM == TN)
+      static_assert(TM == TN && RREADS == RMMAS && LD_REGION <= RMMAS / 2, "region pattern");
+      auto sched_half = [&](bool loads) {
+#pragma unroll
+        for (int i = 0; i < RMMAS; ++i) {
+          __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+          if (i < RMMAS / 2) __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
+          if (loads && i >= RMMAS / 2 && i - RMMAS / 2 < LD_REGION) __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      int sX = 0, sY = 1;
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
+      if (ksteps > 1) {
+        issue_x(1, 2, 0); issue_x(1, 2, 1);
+        issue_y(1, 3, 0); issue_y(1, 3, 1);
+        __builtin_amdgcn_s_waitcnt(wait_vm(2 * A_LD));
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      }
+      __builtin_amdgcn_s_barrier();
+      frags_xy(lds + sX * SLOT, lds + sY * SLOT, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      sA = sA1;
-      sB = sB1;
+      int ks = 0;
+      // Entering K-step ks: X(ks), Y(ks) landed, X(ks+1), Y(ks+1) resident or in flight; the slot of
+      // Y(ks-1) is free (the barrier in the middle of K-step ks-1).
+      for (; ks + 2 < ksteps; ++ks) {
+        const char* cx = lds + sX * SLOT;
+        const char* cy = lds + sY * SLOT;
+        const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
+        const int sX2 = next_slot(sX1, 2);   // slot of X(ks+2) == slot of Y(ks-1)
+        const int sY2 = sX;                  // slot of Y(ks+2) == slot of X(ks)
+        read_x(cx, 1, 1);
+        issue_x(ks + 2, sX2, 0);
+        mma_rows(0, 0, TM / 2);
+        sched_half(true);
+        read_y(cy, 1, 1);
+        issue_x(ks + 2, sX2, 1);
+        mma_rows(0, TM / 2, TM);
+        sched_half(true);
+        // hand-over: everything but X(ks+2) has landed, i.e. X(ks+1) and Y(ks+1) are complete
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_x(lds + sX1 * SLOT, 0, 0);
+        issue_y(ks + 2, sY2, 0);
+        mma_rows(1, 0, TM / 2);
+        sched_half(true);
+        read_y(lds + sY1 * SLOT, 0, 0);
+        issue_y(ks + 2, sY2, 1);
+        mma_rows(1, TM / 2, TM);
+        sched_half(true);
+        sX = sX1;
+        sY = sY1;
+      }
+      // drain: the last two K-steps (their tiles were all requested above or in the prologue)
+      for (; ks < ksteps; ++ks) {
+        const char* cx = lds + sX * SLOT;
+        const char* cy = lds + sY * SLOT;
+        const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
+        const bool more = ks + 1 < ksteps;
+        read_x(cx, 1, 1);
+        mma_rows(0, 0, TM / 2);
+        __builtin_amdgcn_sched_barrier(0);
+        read_y(cy, 1, 1);
+        mma_rows(0, TM / 2, TM);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
+          __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          frags_xy(lds + sX1 * SLOT, lds + sY1 * SLOT, 0, 0);
+        }
+        mma_rows(1, 0, TM);
+        __builtin_amdgcn_sched_barrier(0);
+        sX = sX1;
+        sY = sY1;
+      }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     __builtin_amdgcn_s_barrier();

@@ -1,5 +1,7 @@
 // extern "C" entry points: host-side validation, workspace carving and kernel sequencing.
 // Every argument error is returned before anything is enqueued.
+#include <math.h>
+
 #include "common.h"
 
 using namespace lmhead;
@@ -12,9 +14,16 @@ int validate(const lmhead_desc* d) {
   if (!d) return LMHEAD_E_NULL;
   if (d->P <= 0 || d->G <= 0 || d->T <= 0 || d->d <= 0 || d->V <= 0) return LMHEAD_E_SHAPE;
   if (d->dtype != LMHEAD_F32 && d->dtype != LMHEAD_BF16) return LMHEAD_E_DTYPE;
-  if (d->flags & ~(uint32_t)LMHEAD_FLAG_ACCUM_DW) return LMHEAD_E_DTYPE;
-  if (d->reserved != 0 || d->reserved2 != 0 || d->vocab_chunk < 0) return LMHEAD_E_SHAPE;
+  if (d->flags & ~(uint32_t)(LMHEAD_FLAG_ACCUM_DW | LMHEAD_FLAG_FP8_LOGITS)) return LMHEAD_E_DTYPE;
+  if (d->vocab_chunk < 0) return LMHEAD_E_SHAPE;
   if (d->d % 64 != 0) return LMHEAD_E_SHAPE;
+  if (d->flags & LMHEAD_FLAG_FP8_LOGITS) {
+    // one K-step of the 8-bit kernels is 128 values; exponents beyond +-60 cannot be meant
+    if (d->d % 128 != 0 || d->fp8_exp_h < -60 || d->fp8_exp_h > 60 || d->fp8_exp_w < -60 || d->fp8_exp_w > 60)
+      return LMHEAD_E_SHAPE;
+  } else if (d->fp8_exp_h != 0 || d->fp8_exp_w != 0) {
+    return LMHEAD_E_SHAPE;
+  }
   if (d->ldH < d->d || d->ldW < d->d) return LMHEAD_E_SHAPE;
   const int64_t R = (int64_t)d->P * d->G;
   const int64_t N = R * d->T;
@@ -78,12 +87,31 @@ static int forward(const lmhead_desc* desc, const void* H, const void* const* W,
   LM_TRY(launch_compact(desc->dtype, H, desc->ldH, desc->d, desc->V, tok, nullptr, nullptr, L.N, hdr,
                         w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c), nullptr,
                         nullptr, w.at<float>(L.zy), npol, L.Ncap, s));
+  const bool fp8 = (desc->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
   FwdArgs fa{};
-  fa.Hc = w.at<void>(L.Hc);
-  fa.ldHc = L.ldHc;
-  for (int p = 0; p < kMaxPolicies; ++p) fa.W[p] = W[p < npol ? p : 0];
+  fa.zscale = 1.0f;
+  if (fp8) {
+    // 8-bit copies of the gathered hidden states and of every weight matrix
+    LM_TRY(launch_quantize_e4m3(desc->dtype, w.at<void>(L.Hc), L.ldHc, 0, true, hdr, desc->d, desc->fp8_exp_h,
+                                w.at<void>(L.Hc8), L.ld8, L.Ncap, s));
+    for (int p = 0; p < npol; ++p) {
+      char* w8 = w.at<char>(L.W8) + (size_t)p * L.Vp * L.ld8;
+      LM_TRY(launch_quantize_e4m3(desc->dtype, W[p], desc->ldW, desc->V, false, hdr, desc->d, desc->fp8_exp_w, w8,
+                                  L.ld8, L.Vp, s));
+      fa.W[p] = w8;
+    }
+    for (int p = npol; p < kMaxPolicies; ++p) fa.W[p] = fa.W[0];
+    fa.Hc = w.at<void>(L.Hc8);
+    fa.ldHc = L.ld8;
+    fa.ldW = L.ld8;
+    fa.zscale = ldexpf(1.0f, -(desc->fp8_exp_h + desc->fp8_exp_w));
+  } else {
+    fa.Hc = w.at<void>(L.Hc);
+    fa.ldHc = L.ldHc;
+    for (int p = 0; p < kMaxPolicies; ++p) fa.W[p] = W[p < npol ? p : 0];
+    fa.ldW = desc->ldW;
+  }
   fa.npol = npol;
-  fa.ldW = desc->ldW;
   fa.d = desc->d;
   fa.V = desc->V;
   fa.Ncap = L.Ncap;
@@ -94,7 +122,7 @@ static int forward(const lmhead_desc* desc, const void* H, const void* const* W,
   fa.zy = w.at<float>(L.zy);
   {
     TimedLaunch tl(0, s);
-    LM_TRY(launch_fwd(desc->dtype, fa, s));
+    LM_TRY(launch_fwd(fp8 ? kDtypeFp8 : desc->dtype, fa, s));
   }
   for (int p = 0; p < npol; ++p)
     LM_TRY(launch_finalize(w.at<float>(L.part) + (size_t)p * 3 * L.ntiles * L.Ncap,
@@ -163,6 +191,14 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
   LM_TRY(launch_transpose(dt, W, desc->ldW, desc->V, desc->d, false, hdr, w.at<void>(L.WT), L.ldWT, L.Vp,
                           L.dp, s));
   LM_TRY(launch_zero_padded_rows(dH, desc->d, len, (int)L.R, desc->T, s));
+  const bool fp8 = (desc->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
+  if (fp8) {
+    // the recompute must see the logits the forward saw: same 8-bit copies
+    LM_TRY(launch_quantize_e4m3(dt, w.at<void>(L.Hc), L.ldHc, 0, true, hdr, desc->d, desc->fp8_exp_h,
+                                w.at<void>(L.Hc8), L.ld8, L.Ncap, s));
+    LM_TRY(launch_quantize_e4m3(dt, W, desc->ldW, desc->V, false, hdr, desc->d, desc->fp8_exp_w, w.at<void>(L.W8),
+                                L.ld8, L.Vp, s));
+  }
 
   const int total_tiles = (int)(L.Vp / kTile);
   const int tiles_per_chunk = (int)(L.Vc / kTile);
@@ -171,10 +207,11 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     const int ntiles = (total_tiles - t_lo < tiles_per_chunk) ? total_tiles - t_lo : tiles_per_chunk;
     const int c0 = t_lo * kTile;
     DzArgs za{};
-    za.Hc = w.at<void>(L.Hc);
-    za.ldHc = L.ldHc;
-    za.W = W;
-    za.ldW = desc->ldW;
+    za.Hc = fp8 ? w.at<void>(L.Hc8) : w.at<void>(L.Hc);
+    za.ldHc = fp8 ? L.ld8 : L.ldHc;
+    za.W = fp8 ? w.at<void>(L.W8) : W;
+    za.ldW = fp8 ? L.ld8 : desc->ldW;
+    za.zscale = fp8 ? ldexpf(1.0f, -(desc->fp8_exp_h + desc->fp8_exp_w)) : 1.0f;
     za.d = desc->d;
     za.V = desc->V;
     za.Ncap = L.Ncap;
@@ -190,7 +227,7 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     za.dZT = w.at<void>(L.dZT);
     {
       TimedLaunch tl(1, s);
-      LM_TRY(launch_dz(dt, za, s));
+      LM_TRY(launch_dz(fp8 ? kDtypeFp8 : dt, dt, za, s));
     }
 
     // dH[slot(n)][m] (+)= sum_v W^T[m][c0 + v] dZ[n][v]

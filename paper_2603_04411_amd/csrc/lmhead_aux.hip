@@ -3,6 +3,8 @@
 // softmax statistics, and zero-filling of padded dH rows.  All accesses are coalesced
 // (16-byte vectors where rows allow); none of these kernels is more than a few passes
 // over O(N d + V d) bytes.
+#include <math.h>
+
 #include "common.h"
 
 namespace lmhead {
@@ -167,6 +169,50 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
   }
 }
 
+// ---- 8-bit operand copies ---------------------------------------------------------------
+
+// One wavefront per row: out = e4m3(in * scale), eight values per lane and pass.  The hardware
+// conversion rounds to nearest even but turns magnitudes beyond the format's range into NaN, so
+// values are clamped to +-448 (the largest e4m3 number) first.
+template <typename T>
+__global__ __launch_bounds__(256) void quantize_e4m3_kernel(const T* __restrict__ in, int64_t ld_in,
+                                                            int64_t rows_fixed, int rows_from_nv,
+                                                            const WsHeader* __restrict__ hdr, int cols,
+                                                            float scale, uint8_t* __restrict__ out,
+                                                            int64_t ld_out, int64_t rows_p) {
+  const int64_t rows = rows_from_nv ? (int64_t)hdr->nv : rows_fixed;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows_p) return;
+  if (rows_from_nv && r >= (rows + kTile - 1) / kTile * kTile) return;
+  const int lane = threadIdx.x & 63;
+  for (int c = lane * 8; c < cols; c += 512) {
+    uint2 packed = make_uint2(0u, 0u);
+    if (r < rows) {
+      float v[8];
+      if constexpr (sizeof(T) == 2) {
+        typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+        const bf16x8 t = *reinterpret_cast<const bf16x8*>(in + r * ld_in + c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (float)t[e];
+      } else {
+        const float4 t0 = *reinterpret_cast<const float4*>(in + r * ld_in + c);
+        const float4 t1 = *reinterpret_cast<const float4*>(in + r * ld_in + c + 4);
+        v[0] = t0.x; v[1] = t0.y; v[2] = t0.z; v[3] = t0.w;
+        v[4] = t1.x; v[5] = t1.y; v[6] = t1.z; v[7] = t1.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = fminf(fmaxf(v[e] * scale, -448.f), 448.f);
+      int lo = 0, hi = 0;
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], lo, false);
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], lo, true);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], hi, false);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], hi, true);
+      packed = make_uint2((unsigned)lo, (unsigned)hi);
+    }
+    *reinterpret_cast<uint2*>(out + r * ld_out + c) = packed;
+  }
+}
+
 // ---- merge of per-chunk softmax statistics -------------------------------------------
 
 __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ part,
@@ -258,6 +304,20 @@ hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t ro
                        static_cast<const uint32_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
                        hdr, static_cast<uint32_t*>(out), ld_out, rows_p, cols_p);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3(int dtype, const void* in, int64_t ld_in, int64_t rows_fixed, bool rows_from_nv,
+                                const WsHeader* hdr, int cols, int exp2, void* out, int64_t ld_out, int64_t rows_p,
+                                hipStream_t s) {
+  const dim3 grid((unsigned)((rows_p + 3) / 4));
+  const float scale = ldexpf(1.0f, exp2);
+  if (dtype == LMHEAD_BF16)
+    hipLaunchKernelGGL(quantize_e4m3_kernel<__bf16>, grid, dim3(256), 0, s, static_cast<const __bf16*>(in), ld_in,
+                       rows_fixed, rows_from_nv ? 1 : 0, hdr, cols, scale, static_cast<uint8_t*>(out), ld_out, rows_p);
+  else
+    hipLaunchKernelGGL(quantize_e4m3_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(in), ld_in,
+                       rows_fixed, rows_from_nv ? 1 : 0, hdr, cols, scale, static_cast<uint8_t*>(out), ld_out, rows_p);
   return hipGetLastError();
 }
 

@@ -120,7 +120,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
             zsel = eq ? acc[i][j][v] : zsel;
             found |= eq;
           }
-        if (found) zy[n0 + G::n_of(j)] = zsel;
+        if (found) zy[n0 + G::n_of(j)] = zsel * a.zscale;
       }
     }
   }
@@ -130,6 +130,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   // later blocks from being hoisted, so only 16 values are live in VGPRs at a time
   {
     const int vlim = a.V - m0 - G::m_base();   // vocabulary rows with m_const >= vlim are padding
+    // logit = accumulator * zscale (zscale = 1 unless the operands are scaled 8-bit copies); the factor
+    // is folded into the constants of the block instead of being applied per element
+    const float zscale = a.zscale;
+    const float kz = kLog2e * zscale;
     auto block_stats = [&](auto full_tag, const f32x16_t& blk, int i, float& m_run, float& s_run, float& t_run) {
       constexpr bool kFull = decltype(full_tag)::value;
       float z[16];
@@ -138,19 +142,19 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       float tmax = fmaxf(z[0], z[1]);
 #pragma unroll
       for (int v = 2; v < 16; v += 2) tmax = fmaxf(tmax, fmaxf(z[v], z[v + 1]));
-      const float mn = fmaxf(m_run, tmax);
+      const float mn = fmaxf(m_run, tmax * zscale);
       const float ms = (mn == kNegInf) ? 0.f : mn;
       const float sc = fast_exp2((m_run - ms) * kLog2e);
       const float bias = -ms * kLog2e;
       float ss = 0.f, ts = 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float e = fast_exp2(fmaf(z[v], kLog2e, bias));   // exp2(-inf) = 0 on padding rows
+        const float e = fast_exp2(fmaf(z[v], kz, bias));   // exp2(-inf) = 0 on padding rows
         ss += e;
         ts = fmaf(e, (kFull || G::m_const(i, v) < vlim) ? z[v] : 0.f, ts);
       }
       s_run = fmaf(s_run, sc, ss);
-      t_run = fmaf(t_run, sc, ts);
+      t_run = fmaf(t_run, sc, ts * zscale);
       m_run = mn;
       __builtin_amdgcn_sched_barrier(0);
     };
@@ -218,7 +222,8 @@ struct Store4<f32_tag> {
   __device__ static inline void one(void* p, float a) { *reinterpret_cast<float*>(p) = a; }
 };
 
-template <typename E>
+// E: type of the operands Hc and W (possibly e4m3 copies); EO: type of dZ / dZT.
+template <typename E, typename EO>
 __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   using G = Tile<E, kLeadDz>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -256,7 +261,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   // line-contiguous stores: registers hold 4 consecutive vocabulary entries of one token, which
   // is neither orientation's row.  JG of the wave's TN token blocks are staged per phase (as many
   // as fit next to each other in LDS in both orientations).
-  constexpr int ESZ = Elem<E>::size;
+  constexpr int ESZ = Elem<EO>::size;
   constexpr int JG = ESZ == 2 ? 2 : 1;            // token blocks (of 32) per wave per phase
   constexpr int NTOK = G::WGN * JG * 32;          // tokens staged per phase
   constexpr int P1 = G::BM * ESZ + 16;            // pitch of the [token][vocab] staging rows
@@ -275,6 +280,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
       const int64_t n = n0 + G::n_of(j);
       const float g = a.g_c[n];
       const float bias = -a.lse_c[n] * kLog2e;
+      const float kz = kLog2e * a.zscale;              // logit = accumulator * zscale
       const int rel = a.tok_c[n] - m0 - G::m_base();   // compared with compile-time constants
       const int tl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);   // token within the phase
 #pragma unroll
@@ -284,14 +290,14 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
           float dz[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kLog2e, bias));
+            const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kz, bias));
             const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
             dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
           }
           const int mt = G::m_of(i, 4 * q);   // tile-relative vocabulary row, multiple of 4
-          Store4<E>::row(st1 + tl * P1 + mt * ESZ, dz[0], dz[1], dz[2], dz[3]);
+          Store4<EO>::row(st1 + tl * P1 + mt * ESZ, dz[0], dz[1], dz[2], dz[3]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) Store4<E>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
+          for (int e = 0; e < 4; ++e) Store4<EO>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
         }
     }
     lds_barrier();
@@ -438,34 +444,35 @@ hipError_t allow_lds(K kernel, int bytes) {
 
 }  // namespace
 
-hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s) {
+template <typename E>
+static hipError_t launch_fwd_e(const FwdArgs& a, hipStream_t s) {
+  using G = Tile<E>;
   const dim3 grid(xcd_grid_size(a.ntiles * a.npol, a.Ncap / kTile, kFwdMapBy));
-  hipError_t e;
-  if (dtype == LMHEAD_BF16) {
-    using G = Tile<bf16_tag>;
-    if ((e = allow_lds(fwd_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(fwd_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  } else {
-    using G = Tile<f32_tag>;
-    if ((e = allow_lds(fwd_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(fwd_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  }
+  hipError_t e = allow_lds(fwd_kernel<E>, G::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fwd_kernel<E>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_dz(int dtype, const DzArgs& a, hipStream_t s) {
+hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s) {
+  if (dtype == kDtypeFp8) return launch_fwd_e<fp8_tag>(a, s);
+  return dtype == LMHEAD_BF16 ? launch_fwd_e<bf16_tag>(a, s) : launch_fwd_e<f32_tag>(a, s);
+}
+
+template <typename E, typename EO>
+static hipError_t launch_dz_e(const DzArgs& a, hipStream_t s) {
+  using G = Tile<E>;
   const dim3 grid(xcd_grid_size(a.ntiles, a.Ncap / kTile, kMapBy));
-  hipError_t e;
-  if (dtype == LMHEAD_BF16) {
-    using G = Tile<bf16_tag>;
-    if ((e = allow_lds(dz_kernel<bf16_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(dz_kernel<bf16_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  } else {
-    using G = Tile<f32_tag>;
-    if ((e = allow_lds(dz_kernel<f32_tag>, G::LDS_BYTES)) != hipSuccess) return e;
-    hipLaunchKernelGGL(dz_kernel<f32_tag>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
-  }
+  hipError_t e = allow_lds(dz_kernel<E, EO>, G::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((dz_kernel<E, EO>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();
+}
+
+hipError_t launch_dz(int op_dtype, int out_dtype, const DzArgs& a, hipStream_t s) {
+  if (op_dtype == kDtypeFp8)
+    return out_dtype == LMHEAD_BF16 ? launch_dz_e<fp8_tag, bf16_tag>(a, s) : launch_dz_e<fp8_tag, f32_tag>(a, s);
+  return op_dtype == LMHEAD_BF16 ? launch_dz_e<bf16_tag, bf16_tag>(a, s) : launch_dz_e<f32_tag, f32_tag>(a, s);
 }
 
 template <typename E, int Role>

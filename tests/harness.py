@@ -17,12 +17,13 @@ def to_device(a: np.ndarray):
 class GpuProblem:
     """Device-resident tensors of one workload plus its workspace."""
 
-    def __init__(self, cfg, H, W, tok, lens, vocab_chunk=0, flags=0):
+    def __init__(self, cfg, H, W, tok, lens, vocab_chunk=0, flags=0, fp8_exp_h=0, fp8_exp_w=0):
         import torch
         import paper_2603_04411_amd as L
         self.L = L
         self.cfg = cfg
-        self.desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=vocab_chunk, flags=flags)
+        self.desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=vocab_chunk, flags=flags,
+                                fp8_exp_h=fp8_exp_h, fp8_exp_w=fp8_exp_w)
         assert L.validate_desc(self.desc) == 0
         self.H = to_device(H)
         self.W = to_device(W)

@@ -246,3 +246,40 @@ def test_multi_policy_forward_matches_separate_passes_and_the_oracle():
         assert np.abs(np64(logps[p]) - o_lp).max() <= TOL_LOGP
     two, _, _ = gp.fwd_multi(Ws[:2], want_entropy=False)
     assert bool((two[0] == logps[0]).all()) and bool((two[1] == logps[1]).all())
+
+
+def _fp8_exponent(a):
+    """Largest power of two that keeps max|a| * 2^e inside the e4m3 range."""
+    return int(np.floor(np.log2(448.0 / np.abs(wl.as_f64(a)).max())))
+
+
+@pytest.mark.parametrize("vocab_chunk", [0, 1024])
+def test_fp8_logits_variant(vocab_chunk):
+    """Logits from e4m3 copies of H and W (forward and the backward's recompute), dH / dW contracted with the
+    bf16 operands: against the oracle evaluated on the same rounded copies."""
+    cfg = wl.CONFIGS[1].scaled(P=2, G=4, T=96, d=384, V=4096 + 100)
+    inp = small_inputs(cfg)
+    eh, ew = _fp8_exponent(inp["H"]), _fp8_exponent(inp["W"])
+    assert eh >= 5 and ew >= 10                      # H ~ N(0,1), W ~ N(0, 0.02^2)
+    H64, W64 = wl.as_f64(inp["H"]), wl.as_f64(inp["W"])
+    Hq, Wq = O.quantize_e4m3(H64, eh), O.quantize_e4m3(W64, ew)
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"], vocab_chunk=vocab_chunk, flags=4,
+                    fp8_exp_h=eh, fp8_exp_w=ew)
+    logp, lse, ent, _, _ = gp.fwd()
+    assert gp.check() == 0
+    o_lp, o_lse, o_ent = O.lmhead_logprob_fwd(Hq, Wq, inp["tok"], inp["lens"], cfg.T)
+    for got, want in ((logp, o_lp), (lse, o_lse), (ent, o_ent)):
+        assert np.abs(np64(got) - want).max() <= TOL_LOGP
+    # it is a different function of the inputs than the bf16 path: the two disagree by far more than that
+    b_lp, _, _ = O.lmhead_logprob_fwd(H64, W64, inp["tok"], inp["lens"], cfg.T)
+    assert np.abs(o_lp - b_lp).max() > 2 * TOL_LOGP
+    g = wl.synthetic_upstream_grad(cfg, inp["lens"])
+    dH, dW = gp.bwd(lse, to_device(g))
+    o_dH, o_dW = O.lmhead_logprob_bwd(H64, W64, inp["tok"], inp["lens"], cfg.T, g, H_logits=Hq, W_logits=Wq)
+    e_h, e_w = rel_fro(np64(dH), o_dH), rel_fro(np64(dW), o_dW)
+    assert e_h <= TOL_GRAD and e_w <= TOL_GRAD, (e_h, e_w)
+    # the multi-policy pass takes the same route
+    logps, lse2, _ = GpuProblem.fwd_multi(gp, [gp.W, to_device(inp["W_ref"])], want_entropy=False)
+    assert bool((logps[0] == logp).all()) and bool((lse2 == lse).all())
+    o_ref, _, _ = O.lmhead_logprob_fwd(Hq, O.quantize_e4m3(wl.as_f64(inp["W_ref"]), ew), inp["tok"], inp["lens"], cfg.T)
+    assert np.abs(np64(logps[1]) - o_ref).max() <= TOL_LOGP

@@ -53,6 +53,8 @@ def test_descriptor_validation_codes(lib):
         (dict(P=0), -2), (dict(T=-1), -2), (dict(V=0), -2), (dict(d=250), -2), (dict(d=0), -2),
         (dict(ldH=128), -2), (dict(ldW=255), -2), (dict(dtype=7), -3), (dict(flags=1 << 9), -3),
         (dict(vocab_chunk=-5), -2), (dict(P=70000, G=70000), -2), (dict(ldH=258), -4),
+        (dict(fp8_exp_h=3), -2), (dict(fp8_exp_w=-1), -2),                      # exponents without the flag
+        (dict(flags=4, d=192, ldH=192, ldW=192), -2), (dict(flags=4, fp8_exp_w=99), -2),
     ]
     for change, code in cases:
         kw = dict(P=2, G=4, T=32, d=256, V=4096, dtype="f32")
@@ -61,6 +63,9 @@ def test_descriptor_validation_codes(lib):
         assert L.validate_desc(desc) == code, (change, L.validate_desc(desc))
         assert L.workspace_bytes(desc) == 0
     assert lib.lmhead_validate_desc(None) == -1
+    fp8 = L.make_desc(2, 4, 32, 256, 4096, "bf16", flags=4, fp8_exp_h=6, fp8_exp_w=12)
+    plain = L.make_desc(2, 4, 32, 256, 4096, "bf16")
+    assert L.validate_desc(fp8) == 0 and L.workspace_bytes(fp8) > L.workspace_bytes(plain)
 
 
 def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
