@@ -85,6 +85,11 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     const int row = G::ldB_row(q);
     offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
   }
+  // target ids of this lane's token columns: fetched before the main loop so that their latency is hidden
+  int tkj[G::TN];
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) tkj[j] = a.tok_c[n0 + G::n_of(j)];
+
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, Wp + (int64_t)m0 * pitchW, offA, static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     bool hit = false;
 #pragma unroll
     for (int j = 0; j < G::TN; ++j) {
-      const int tk = a.tok_c[n0 + G::n_of(j)];
+      const int tk = tkj[j];
       hit |= (tk >= m0) & (tk < m0 + G::BM);
       relj[j] = tk - m0 - G::m_base();   // compared with compile-time constants
     }
@@ -250,6 +255,20 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
     offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
   }
 
+  // per-token scalars of this lane's token columns, fetched before the main loop (latency hidden)
+  float gj[G::TN], biasj[G::TN];
+  int relj[G::TN];
+  bool hit = false;
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const int64_t n = n0 + G::n_of(j);
+    gj[j] = a.g_c[n];
+    biasj[j] = -a.lse_c[n] * kLog2e;
+    const int tk = a.tok_c[n];
+    hit |= (tk >= m0) & (tk < m0 + G::BM);
+    relj[j] = tk - m0 - G::m_base();   // compared with compile-time constants
+  }
+
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
@@ -272,33 +291,47 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   char* st1 = smem;
   char* st2 = smem + L2_OFF;
   const int vlim = a.V - m0 - G::m_base();
+  const float kz = kLog2e * a.zscale;              // logit = accumulator * zscale
+  // Most tiles hold no target token of the wave's columns and no padding rows: there dZ = -g p with no
+  // per-element tests.  (Wave-uniform choice.)
+  const bool plain = !__any(hit) && (m0 + G::BM <= a.V);
 #pragma unroll
   for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj) {
       const int j = jg * JG + jj;
-      const int64_t n = n0 + G::n_of(j);
-      const float g = a.g_c[n];
-      const float bias = -a.lse_c[n] * kLog2e;
-      const float kz = kLog2e * a.zscale;              // logit = accumulator * zscale
-      const int rel = a.tok_c[n] - m0 - G::m_base();   // compared with compile-time constants
+      const float g = gj[j];
+      const float bias = biasj[j];
+      const int rel = relj[j];
       const int tl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);   // token within the phase
+      auto emit = [&](auto plain_tag) {
+        constexpr bool kPlain = decltype(plain_tag)::value;
+        const float ng = -g;
 #pragma unroll
-      for (int i = 0; i < G::TM; ++i)
+        for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float dz[4];
+          for (int q = 0; q < 4; ++q) {
+            float dz[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kz, bias));
-            const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
-            dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
+            for (int e = 0; e < 4; ++e) {
+              const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kz, bias));
+              if constexpr (kPlain) {
+                dz[e] = ng * p;
+              } else {
+                const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
+                dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
+              }
+            }
+            const int mt = G::m_of(i, 4 * q);   // tile-relative vocabulary row, multiple of 4
+            Store4<EO>::row(st1 + tl * P1 + mt * ESZ, dz[0], dz[1], dz[2], dz[3]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Store4<EO>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
           }
-          const int mt = G::m_of(i, 4 * q);   // tile-relative vocabulary row, multiple of 4
-          Store4<EO>::row(st1 + tl * P1 + mt * ESZ, dz[0], dz[1], dz[2], dz[3]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) Store4<EO>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
-        }
+      };
+      if (plain)
+        emit(std::true_type{});
+      else
+        emit(std::false_type{});
     }
     lds_barrier();
     // [token][vocab] rows -> dZ: one staged row is BM*ESZ contiguous bytes of a dZ row
