@@ -102,7 +102,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the target config)")
     ap.add_argument("--vocab-chunk", type=int, default=0)
-    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the oracle sample (0 = skip)")
     ap.add_argument("--separate-forwards", action="store_true",
                     help="where the step recomputes old/reference log-probs, use one forward call per policy "
                          "instead of the single multi-policy pass (for comparison)")

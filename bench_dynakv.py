@@ -85,7 +85,7 @@ def main(argv=None) -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="index into workloads.dynakv.KV_CONFIGS")
-    ap.add_argument("--cpu-rows", type=int, default=2048, help="tokens of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=32768, help="tokens of the oracle sample (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true")
     args = ap.parse_args(argv)
     if args.gpus != 1:
