@@ -47,18 +47,22 @@ struct WsLayout {
   // channel and set (the token-major operands have a pitch of Ncap elements, often 2^k).
   int64_t ldHc, ldHcT, ldWT, ldZ, ldZT;
   int64_t ld8;      // pitch (bytes) of the e4m3 operand copies: d + one 128-byte line
+  int ksplit;       // dH: slices of the contraction per output tile (> 1 only when the tile grid
+                    // alone would leave most of the chip idle); partial tiles go to dHpart
+  size_t dHpart;
   size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, Hc8, W8, total;
 };
 
 // Default backward chunk: as wide as keeps the two dZ copies (worst case: every slot valid)
-// within about 48 GB, at most 32768 columns.  Wider chunks mean fewer read-modify-write
-// passes over dH and longer contractions per launch.
+// within about 48 GB, at most 262144 columns (small problems take the whole vocabulary in one
+// chunk).  Wider chunks mean fewer read-modify-write passes over dH and longer contractions per
+// launch.
 static inline int64_t default_vocab_chunk(const lmhead_desc* d) {
   const int64_t esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
   const int64_t N = (int64_t)d->P * d->G * d->T;
   int64_t vc = (48ll << 30) / (2 * esz * (N > 0 ? N : 1));
   vc = vc / kTile * kTile;
-  if (vc > 32768) vc = 32768;
+  if (vc > 262144) vc = 262144;
   if (vc < 4 * kTile) vc = 4 * kTile;
   return vc;
 }
@@ -108,6 +112,16 @@ static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
   L.WT = take((size_t)L.dp * L.ldWT * L.esz);
   L.dZ = take((size_t)L.Ncap * L.ldZ * L.esz);
   L.dZT = take((size_t)L.Vc * L.ldZT * L.esz);
+  // dH has (d / 256) x (tokens / 256) output tiles.  Below about four per compute unit the last
+  // round of workgroups is mostly empty, so the contraction of each tile is cut into ksplit slices
+  // that run as separate workgroups and are summed afterwards in a fixed order.
+  {
+    const int64_t tiles = (L.dp / kTile) * (L.Ncap / kTile);
+    int64_t ks = tiles >= 1024 ? 1 : (1536 + tiles - 1) / tiles;
+    if (ks > 8) ks = 8;
+    L.ksplit = (int)ks;
+    L.dHpart = take(ks > 1 ? (size_t)ks * L.Ncap * L.dp * 4 : 0);
+  }
   L.ld8 = d->d + 128;
   const bool fp8 = (d->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
   L.Hc8 = take(fp8 ? (size_t)L.Ncap * L.ld8 : 0);
@@ -205,7 +219,16 @@ struct GemmTArgs {
   bool accumulate;
   int64_t n_tiles_cap; // grid extent over n
   const WsHeader* hdr;
+  int ksplit;          // > 1: slice s of the contraction writes its tile to part[s][n][m] (dense
+  float* part;         // rows of part_ld floats, no row map, no accumulation); launch_splitk_reduce
+  int64_t part_ld;     // then forms out.  part_slice = floats per slice.
+  int64_t part_slice;
 };
+
+// out[rowmap(n)][m] (+)= sum_s part[s][n][m] for n < header.nv, m < M, slices summed in order.
+hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
+                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, float* out, int64_t ldo,
+                                bool accumulate, hipStream_t s);
 hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s);
 
 // Rows of dH that belong to padded slots are set to 0.

@@ -246,9 +246,16 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     ha.accumulate = c > 0;
     ha.n_tiles_cap = L.Ncap / kTile;
     ha.hdr = hdr;
+    ha.ksplit = L.ksplit;
+    ha.part = w.at<float>(L.dHpart);
+    ha.part_ld = L.dp;
+    ha.part_slice = L.Ncap * L.dp;
     {
       TimedLaunch tl(2, s);
       LM_TRY(launch_gemm_t(dt, ha, s));
+      if (L.ksplit > 1)
+        LM_TRY(launch_splitk_reduce(ha.part, L.ksplit, ha.part_slice, ha.part_ld, desc->d, ha.rowmap, hdr, L.Ncap,
+                                    dH, desc->d, c > 0, s));
     }
 
     // dW[c0 + n][m] = sum_i Hc^T[m][i] dZ^T[n][i]
@@ -268,6 +275,7 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     wa.accumulate = (desc->flags & LMHEAD_FLAG_ACCUM_DW) != 0;
     wa.n_tiles_cap = ntiles;
     wa.hdr = hdr;
+    wa.ksplit = 1;
     {
       TimedLaunch tl(3, s);
       LM_TRY(launch_gemm_t(dt, wa, s));

@@ -251,6 +251,34 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
   if (ent) ent[i] = o_ent;
 }
 
+// ---- sum of split contractions -----------------------------------------------------------
+
+// One wavefront per valid row n: out[rowmap(n)][:] (+)= part[0][n][:] + part[1][n][:] + ... (in this order).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int ksplit,
+                                                            int64_t part_slice, int64_t part_ld, int M,
+                                                            const int32_t* __restrict__ rowmap,
+                                                            const WsHeader* __restrict__ hdr,
+                                                            float* __restrict__ out, int64_t ldo, int accumulate) {
+  const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= hdr->nv) return;
+  const int64_t row = rowmap[n];
+  if (row < 0) return;
+  const int lane = threadIdx.x & 63;
+  for (int m = lane * 4; m < M; m += 256) {
+    float4 v = *reinterpret_cast<const float4*>(part + n * part_ld + m);
+    for (int s = 1; s < ksplit; ++s) {
+      const float4 p = *reinterpret_cast<const float4*>(part + (size_t)s * part_slice + n * part_ld + m);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    float4* dst = reinterpret_cast<float4*>(out + row * ldo + m);
+    if (accumulate) {
+      const float4 o = *dst;
+      v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+    }
+    *dst = v;
+  }
+}
+
 // ---- padded rows of dH -------------------------------------------------------------------
 
 // One wavefront per slot; only padded slots write.
@@ -318,6 +346,14 @@ hipError_t launch_quantize_e4m3(int dtype, const void* in, int64_t ld_in, int64_
   else
     hipLaunchKernelGGL(quantize_e4m3_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(in), ld_in,
                        rows_fixed, rows_from_nv ? 1 : 0, hdr, cols, scale, static_cast<uint8_t*>(out), ld_out, rows_p);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
+                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, float* out, int64_t ldo,
+                                bool accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n_cap + 3) / 4)), dim3(256), 0, s, part, ksplit,
+                     part_slice, part_ld, M, rowmap, hdr, out, ldo, accumulate ? 1 : 0);
   return hipGetLastError();
 }
 

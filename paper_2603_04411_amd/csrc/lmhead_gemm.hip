@@ -374,14 +374,19 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nv = a.hdr->nv;
   const int64_t n_lim = a.n_from_nv ? (int64_t)nv : a.n_limit;
-  int mt, nt;
-  if (!xcd_tile_coords(blockIdx.x, (a.M + G::BM - 1) / G::BM, (int)((n_lim + G::BN - 1) / G::BN), kMapBx, kMapBy,
-                       mt, nt))
-    return;
+  // the walk's y axis runs over (slice of the contraction, n tile): neighbours share the slice's K range
+  const int ntiles = (int)((n_lim + G::BN - 1) / G::BN);
+  int mt, ny;
+  if (!xcd_tile_coords(blockIdx.x, (a.M + G::BM - 1) / G::BM, ntiles * a.ksplit, kMapBx, kMapBy, mt, ny)) return;
+  const int slice = ny / ntiles;
+  const int nt = ny - slice * ntiles;
   const int64_t n0 = (int64_t)nt * G::BN;
   const int m0 = mt * G::BM;
   const int64_t kel = a.k_from_nv ? (int64_t)nv : a.K;
-  const int ksteps = (int)((kel * Elem<E>::size + G::KB - 1) / G::KB);
+  const int ksteps_all = (int)((kel * Elem<E>::size + G::KB - 1) / G::KB);
+  const int per_slice = (ksteps_all + a.ksplit - 1) / a.ksplit;
+  const int k_first = slice * per_slice;
+  const int ksteps = max(0, min(per_slice, ksteps_all - k_first));
   const int64_t pitchA = a.ldA * Elem<E>::size;
   const int64_t pitchB = a.ldB * Elem<E>::size;
 
@@ -410,14 +415,17 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
     const int r = G::wave() + G::NWAVES * i;
     const int64_t n = n0 + (r / (JG * 32)) * G::WN + p * (JG * 32) + r % (JG * 32);
     int64_t row = -1;
-    if (n < n_lim) row = a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n;
+    if (n < n_lim) row = a.ksplit > 1 ? n : (a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n);
     my_row = (int)row;
   }
+  float* const outp = a.ksplit > 1 ? a.part + (size_t)slice * a.part_slice : a.out;
+  const int64_t ldo = a.ksplit > 1 ? a.part_ld : a.ldo;
+  const bool accumulate = a.ksplit > 1 ? false : a.accumulate;
 
   typename G::Acc acc;
   G::zero(acc);
-  G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA,
-         static_cast<const char*>(a.B) + n0 * pitchB, offB, ksteps, smem);
+  G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA + (int64_t)k_first * G::KB, offA,
+         static_cast<const char*>(a.B) + n0 * pitchB + (int64_t)k_first * G::KB, offB, ksteps, smem);
 
   // The fp32 tile leaves through LDS as [n][m] rows, so that each output row segment (BM floats
   // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.  Rows go in
@@ -452,10 +460,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
 #pragma unroll
       for (int u = 0; u < RB; ++u) {
         const int64_t row = __builtin_amdgcn_readlane(my_row, jg * ROWS_PER_WAVE + i0 + u);
-        dst[u] = (row >= 0 && m_ok) ? reinterpret_cast<f32x4_t*>(a.out + row * a.ldo + m) : nullptr;
+        dst[u] = (row >= 0 && m_ok) ? reinterpret_cast<f32x4_t*>(outp + row * ldo + m) : nullptr;
         v[u] = *reinterpret_cast<const f32x4_t*>(smem + (G::wave() + G::NWAVES * (i0 + u)) * P + c * 16);
       }
-      if (a.accumulate) {
+      if (accumulate) {
 #pragma unroll
         for (int u = 0; u < RB; ++u) old[u] = dst[u] ? *dst[u] : f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -511,7 +519,7 @@ hipError_t launch_dz(int op_dtype, int out_dtype, const DzArgs& a, hipStream_t s
 template <typename E, int Role>
 static hipError_t launch_gemm_t_impl(const GemmTArgs& a, hipStream_t s) {
   using G = Tile<E>;
-  const dim3 grid(xcd_grid_size((a.M + kTile - 1) / kTile, a.n_tiles_cap, kMapBy));
+  const dim3 grid(xcd_grid_size((a.M + kTile - 1) / kTile, a.n_tiles_cap * a.ksplit, kMapBy));
   hipError_t e = allow_lds(gemm_t_kernel<E, Role>, G::LDS_BYTES);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_t_kernel<E, Role>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
