@@ -62,7 +62,7 @@ TimingState g_timing;
 
 extern "C" {
 
-int lmhead_abi_version(void) { return 1; }
+int lmhead_abi_version(void) { return 2; }
 
 int lmhead_validate_desc(const lmhead_desc* desc) { return validate(desc); }
 
