@@ -1,7 +1,8 @@
 // MFMA macro-tile main loop shared by every contraction of the library (gfx950).
 //
-// All four contractions (logits, logits recompute for dZ, dH, dW) are brought to the
-// same form  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands K-contiguous.
+// All contractions (logits, logits recompute for dZ, dH, dW; the KV path's spectral projection,
+// gate logits and ragged reconstruction) are brought to the same form
+// C[m][n] = sum_k A[m][k] * B[n][k]  with both operands K-contiguous.
 // A workgroup owns a BM x BN tile of C; each wavefront owns a (BM/WGM) x (BN/WGN)
 // sub-tile built from 32x32 MFMA blocks.
 //

@@ -1,6 +1,6 @@
 // Bandwidth-bound helper kernels around the MFMA kernels: batch indexing (mask, prefix
-// sums, compaction map), row gather of H, operand transposes, the per-chunk merge of the
-// softmax statistics, and zero-filling of padded dH rows.  All accesses are coalesced
+// sums, compaction map), row gather of H, operand transposes, 8-bit operand copies, the merge of
+// the per-tile softmax statistics, the sum of split dH contractions, and zero-filling of padded dH rows.  All accesses are coalesced
 // (16-byte vectors where rows allow); none of these kernels is more than a few passes
 // over O(N d + V d) bytes.
 #include <math.h>

@@ -1,8 +1,9 @@
-// The three MFMA kernels of the library, all built on GemmTile (gemm_core.h):
+// The three MFMA kernels of the LM-head path, all built on GemmTile (gemm_core.h):
 //   fwd_kernel    logits tile (vocabulary x tokens) -> max / sum-exp / sum-exp*z per token and tile,
 //                 target-logit capture; nothing of the tile is stored           (log-softmax of L_CE, Eq. 9)
 //   dz_kernel     logits tile recomputed -> dZ = g (onehot - softmax), stored in both orientations
 //   gemm_t_kernel plain contraction with a transposed, row-mapped fp32 store    (dH and dW)
+// fwd_kernel and dz_kernel also exist for 8-bit (e4m3) copies of their operands.
 //
 // Orientation: the vocabulary (or d) runs along the MFMA M axis and tokens (or vocabulary
 // rows of dW) along N.  With the 32x32 accumulator layout a lane then owns ONE token column
