@@ -125,3 +125,42 @@ def test_full_size(ci):
     e_h2 = rel_fro(np64(s_dH), o_dH_rows)
     say(f"[full]   sub-problem: dW rel err {e_w:.2e}, dH rel err {e_h2:.2e}")
     assert e_w <= 1e-2 and e_h2 <= 1e-2
+
+
+def test_full_size_fp8_logits_variant():
+    """configs[2] with the logits kernels on e4m3 copies: sampled rows against the oracle evaluated on the
+    same rounded copies, and the identities that still tie the complete dH and dW together."""
+    import torch
+    cfg = wl.CONFIGS[2]
+    lens, tok = wl.lengths(cfg), wl.tokens(cfg)
+    H_host, W_host = wl.hidden(cfg), wl.weight(cfg)
+    eh = int(np.floor(np.log2(448.0 / np.abs(wl.as_f64(H_host[:65536])).max()))) - 1
+    ew = int(np.floor(np.log2(448.0 / np.abs(wl.as_f64(W_host[:65536])).max()))) - 1
+    gp = GpuProblem(cfg, H_host, W_host, tok, lens, flags=4, fp8_exp_h=eh, fp8_exp_w=ew)
+    logp, lse, ent, _, _ = gp.fwd()
+    assert gp.check() == 0
+    rows = wl.sample_valid_rows(cfg, lens, tok, SAMPLE)
+    Hs, W64 = wl.as_f64(H_host[rows]), wl.as_f64(W_host)
+    Hq, Wq = O.quantize_e4m3(Hs, eh), O.quantize_e4m3(W64, ew)
+    assert np.abs(Hq).max() * 2.0 ** eh <= 448 and np.abs(Wq).max() * 2.0 ** ew <= 448
+    o_lp, o_lse, o_ent = O.logprob_rows(Hq, Wq, tok[rows])
+    ridx = torch.from_numpy(rows).cuda()
+    for got, want, name in ((logp, o_lp, "logp"), (lse, o_lse, "lse"), (ent, o_ent, "entropy")):
+        err = np.abs(np64(got[ridx]) - want).max()
+        say(f"[full fp8]   {name}: max abs err on {rows.size} rows {err:.2e}")
+        assert err <= 1e-2
+    g_host = wl.synthetic_upstream_grad(cfg, lens)
+    dH, dW = gp.bwd(lse, to_device(g_host))
+    assert gp.check() == 0
+    o_dH_rows, _ = O.bwd_rows(Hs, W64, tok[rows], g_host[rows].astype(np.float64), Hq, Wq)
+    e_h = rel_fro(np64(dH[ridx]), o_dH_rows)
+    say(f"[full fp8]   dH on sampled rows: rel Frobenius err {e_h:.2e}")
+    assert e_h <= 1e-2
+    colsum = dW.double().sum(dim=0)
+    dw_scale = dW.double().abs().sum(dim=0)
+    assert float((colsum.abs() / (dw_scale + 1e-30)).max()) <= 1e-3
+    lhs_w = sum(float((dW[v0:v0 + 16384].double() * gp.W[v0:v0 + 16384].double()).sum()) for v0 in range(0, cfg.V, 16384))
+    lhs_h = sum(float((dH[n0:n0 + 32768].double() * gp.H[n0:n0 + 32768].double()).sum()) for n0 in range(0, cfg.N, 32768))
+    scale = float((dH.double().abs() * gp.H.double().abs()).sum())
+    say(f"[full fp8]   <dW,W> {lhs_w:.6e}  <dH,H> {lhs_h:.6e}  (scale {scale:.3e})")
+    assert abs(lhs_w - lhs_h) <= 1e-3 * scale
