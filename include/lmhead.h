@@ -63,6 +63,8 @@ enum { LMHEAD_F32 = 0, LMHEAD_BF16 = 1 };
 
 enum {
   LMHEAD_FLAG_ACCUM_DW = 1u << 1,   /* lmhead_logprob_bwd adds into dW instead of overwriting it */
+  LMHEAD_FLAG_DH_BF16 = 1u << 3,    /* lmhead_logprob_bwd writes dH as bf16 [N x d] (accumulated in fp32 */
+                                    /* scratch over the vocabulary chunks, rounded once at the end)       */
   LMHEAD_FLAG_FP8_LOGITS = 1u << 2  /* logits (forward and the backward's recompute) from 8-bit copies */
                                     /* of H and W: OCP e4m3, x * 2^fp8_exp rounded to nearest even and  */
                                     /* clamped to +-448, fp32 accumulation; dH and dW still contract    */
@@ -137,14 +139,15 @@ LMHEAD_API int lmhead_logprob_fwd_multi(const lmhead_desc* desc, const void* H, 
  * Backward through the same chunked softmax.  Given g_logp[i] = dL/dlogp_i (0 on
  * padding) and the lse saved by the forward:
  *     dZ[i,v] = g_i (1[v == y_i] - exp(z[i,v] - lse_i))     (recomputed per vocabulary chunk)
- *     dH[i,:] = sum_v dZ[i,v] W[v,:]         float[N x d], dense row stride d; padded rows = 0
+ *     dH[i,:] = sum_v dZ[i,v] W[v,:]         float[N x d] (bf16 with LMHEAD_FLAG_DH_BF16), dense row stride d;
+ *                                            padded rows = 0
  *     dW[v,:] = sum_i dZ[i,v] H[i,:]         float[V x d], dense row stride d
  * With LMHEAD_FLAG_ACCUM_DW the result is added to the contents of dW.
  */
 LMHEAD_API int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W,
                        const int32_t* tok, const int32_t* len,
                        const float* lse, const float* g_logp,
-                       float* dH, float* dW,
+                       void* dH, float* dW,
                        void* ws, size_t ws_bytes, void* stream);
 
 /*

@@ -30,6 +30,7 @@ LMHEAD_F32 = 0
 LMHEAD_BF16 = 1
 FLAG_ACCUM_DW = 1 << 1
 FLAG_FP8_LOGITS = 1 << 2
+FLAG_DH_BF16 = 1 << 3
 
 
 class LmheadError(RuntimeError):

@@ -120,7 +120,9 @@ static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
     int64_t ks = tiles >= 1024 ? 1 : (1536 + tiles - 1) / tiles;
     if (ks > 8) ks = 8;
     L.ksplit = (int)ks;
-    L.dHpart = take(ks > 1 ? (size_t)ks * L.Ncap * L.dp * 4 : 0);
+    // a bf16 dH is accumulated in these fp32 buffers too and rounded once at the end
+    const bool need = ks > 1 || (d->flags & LMHEAD_FLAG_DH_BF16) != 0;
+    L.dHpart = take(need ? (size_t)ks * L.Ncap * L.dp * 4 : 0);
   }
   L.ld8 = d->d + 128;
   const bool fp8 = (d->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
@@ -219,20 +221,22 @@ struct GemmTArgs {
   bool accumulate;
   int64_t n_tiles_cap; // grid extent over n
   const WsHeader* hdr;
-  int ksplit;          // > 1: slice s of the contraction writes its tile to part[s][n][m] (dense
-  float* part;         // rows of part_ld floats, no row map, no accumulation); launch_splitk_reduce
-  int64_t part_ld;     // then forms out.  part_slice = floats per slice.
-  int64_t part_slice;
+  int ksplit;          // slices of the contraction per output tile (>= 1)
+  float* part;         // non-null: slice s writes (part_accumulate: adds) its tile to part[s][n][m], dense
+  int64_t part_ld;     // rows of part_ld floats without the row map, and launch_splitk_reduce forms out
+  int64_t part_slice;  // from the slices.  part_slice = floats per slice.  Required when ksplit > 1.
+  bool part_accumulate;
 };
 
 // out[rowmap(n)][m] (+)= sum_s part[s][n][m] for n < header.nv, m < M, slices summed in order.
+// out is float, or bf16 when out_bf16 (then accumulate must be false).
 hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
-                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, float* out, int64_t ldo,
-                                bool accumulate, hipStream_t s);
+                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, void* out, int64_t ldo,
+                                bool accumulate, bool out_bf16, hipStream_t s);
 hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s);
 
 // Rows of dH that belong to padded slots are set to 0.
-hipError_t launch_zero_padded_rows(float* dH, int d, const int32_t* len, int R, int T,
+hipError_t launch_zero_padded_rows(void* dH, bool bf16, int d, const int32_t* len, int R, int T,
                                    hipStream_t s);
 
 hipError_t launch_group_advantage(const float* reward, int P, int G, float eps, int ddof,

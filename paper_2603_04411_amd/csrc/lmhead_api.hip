@@ -14,7 +14,7 @@ int validate(const lmhead_desc* d) {
   if (!d) return LMHEAD_E_NULL;
   if (d->P <= 0 || d->G <= 0 || d->T <= 0 || d->d <= 0 || d->V <= 0) return LMHEAD_E_SHAPE;
   if (d->dtype != LMHEAD_F32 && d->dtype != LMHEAD_BF16) return LMHEAD_E_DTYPE;
-  if (d->flags & ~(uint32_t)(LMHEAD_FLAG_ACCUM_DW | LMHEAD_FLAG_FP8_LOGITS)) return LMHEAD_E_DTYPE;
+  if (d->flags & ~(uint32_t)(LMHEAD_FLAG_ACCUM_DW | LMHEAD_FLAG_FP8_LOGITS | LMHEAD_FLAG_DH_BF16)) return LMHEAD_E_DTYPE;
   if (d->vocab_chunk < 0) return LMHEAD_E_SHAPE;
   if (d->d % 64 != 0) return LMHEAD_E_SHAPE;
   if (d->flags & LMHEAD_FLAG_FP8_LOGITS) {
@@ -165,7 +165,7 @@ int lmhead_logprob_fwd_multi(const lmhead_desc* desc, const void* H, const void*
 }
 
 int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, const int32_t* tok,
-                       const int32_t* len, const float* lse, const float* g_logp, float* dH, float* dW,
+                       const int32_t* len, const float* lse, const float* g_logp, void* dH, float* dW,
                        void* ws, size_t ws_bytes, void* stream) {
   const int rc = validate(desc);
   if (rc != LMHEAD_OK) return rc;
@@ -190,7 +190,8 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
                           L.ldHcT, L.Ncap, L.dp, s));
   LM_TRY(launch_transpose(dt, W, desc->ldW, desc->V, desc->d, false, hdr, w.at<void>(L.WT), L.ldWT, L.Vp,
                           L.dp, s));
-  LM_TRY(launch_zero_padded_rows(dH, desc->d, len, (int)L.R, desc->T, s));
+  const bool dh16 = (desc->flags & LMHEAD_FLAG_DH_BF16) != 0;
+  LM_TRY(launch_zero_padded_rows(dH, dh16, desc->d, len, (int)L.R, desc->T, s));
   const bool fp8 = (desc->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
   if (fp8) {
     // the recompute must see the logits the forward saw: same 8-bit copies
@@ -241,21 +242,27 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     ha.k_from_nv = false;
     ha.K = (int64_t)ntiles * kTile;
     ha.rowmap = w.at<int32_t>(L.row_slot);
-    ha.out = dH;
+    ha.out = static_cast<float*>(dH);   // unused when the tiles go to the fp32 scratch slices
     ha.ldo = desc->d;
     ha.accumulate = c > 0;
     ha.n_tiles_cap = L.Ncap / kTile;
     ha.hdr = hdr;
     ha.ksplit = L.ksplit;
-    ha.part = w.at<float>(L.dHpart);
+    ha.part = (L.ksplit > 1 || dh16) ? w.at<float>(L.dHpart) : nullptr;
     ha.part_ld = L.dp;
     ha.part_slice = L.Ncap * L.dp;
+    ha.part_accumulate = dh16 && c > 0;   // a bf16 dH is summed over the chunks in the scratch slices
     {
       TimedLaunch tl(2, s);
       LM_TRY(launch_gemm_t(dt, ha, s));
-      if (L.ksplit > 1)
+      if (dh16) {
+        if (c + 1 == (int)L.nchunks)
+          LM_TRY(launch_splitk_reduce(ha.part, L.ksplit, ha.part_slice, ha.part_ld, desc->d, ha.rowmap, hdr,
+                                      L.Ncap, dH, desc->d, false, true, s));
+      } else if (L.ksplit > 1) {
         LM_TRY(launch_splitk_reduce(ha.part, L.ksplit, ha.part_slice, ha.part_ld, desc->d, ha.rowmap, hdr, L.Ncap,
-                                    dH, desc->d, c > 0, s));
+                                    dH, desc->d, c > 0, false, s));
+      }
     }
 
     // dW[c0 + n][m] = sum_i Hc^T[m][i] dZ^T[n][i]
@@ -276,6 +283,7 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     wa.n_tiles_cap = ntiles;
     wa.hdr = hdr;
     wa.ksplit = 1;
+    wa.part = nullptr;
     {
       TimedLaunch tl(3, s);
       LM_TRY(launch_gemm_t(dt, wa, s));

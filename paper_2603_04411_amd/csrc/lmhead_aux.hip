@@ -254,11 +254,12 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
 // ---- sum of split contractions -----------------------------------------------------------
 
 // One wavefront per valid row n: out[rowmap(n)][:] (+)= part[0][n][:] + part[1][n][:] + ... (in this order).
+template <typename TO>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int ksplit,
                                                             int64_t part_slice, int64_t part_ld, int M,
                                                             const int32_t* __restrict__ rowmap,
                                                             const WsHeader* __restrict__ hdr,
-                                                            float* __restrict__ out, int64_t ldo, int accumulate) {
+                                                            TO* __restrict__ out, int64_t ldo, int accumulate) {
   const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= hdr->nv) return;
   const int64_t row = rowmap[n];
@@ -270,19 +271,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
       const float4 p = *reinterpret_cast<const float4*>(part + (size_t)s * part_slice + n * part_ld + m);
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }
-    float4* dst = reinterpret_cast<float4*>(out + row * ldo + m);
-    if (accumulate) {
-      const float4 o = *dst;
-      v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+    if constexpr (sizeof(TO) == 4) {
+      float4* dst = reinterpret_cast<float4*>(out + row * ldo + m);
+      if (accumulate) {
+        const float4 o = *dst;
+        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+      }
+      *dst = v;
+    } else {
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+      const bf16x4_t h = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+      *reinterpret_cast<bf16x4_t*>(out + row * ldo + m) = h;
     }
-    *dst = v;
   }
 }
 
 // ---- padded rows of dH -------------------------------------------------------------------
 
 // One wavefront per slot; only padded slots write.
-__global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ dH, int d,
+template <typename TO>
+__global__ __launch_bounds__(256) void zero_rows_kernel(TO* __restrict__ dH, int d,
                                                         const int32_t* __restrict__ len, int R, int T) {
   const int64_t N = (int64_t)R * T;
   const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -290,10 +298,10 @@ __global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ dH, 
   const int r = (int)(i / T);
   const int t = (int)(i - (int64_t)r * T);
   if (t < min(max(len[r], 0), T)) return;
-  typedef __attribute__((ext_vector_type(4))) float f4;
+  typedef __attribute__((ext_vector_type(4))) float f4;    // 16 bytes of zeros, whatever the element type
   f4* row = reinterpret_cast<f4*>(dH + i * (int64_t)d);
   const f4 z = {0.f, 0.f, 0.f, 0.f};
-  for (int c = threadIdx.x & 63; c < d / 4; c += 64) row[c] = z;
+  for (int c = threadIdx.x & 63; c < d * (int)sizeof(TO) / 16; c += 64) row[c] = z;
 }
 
 }  // namespace
@@ -350,10 +358,15 @@ hipError_t launch_quantize_e4m3(int dtype, const void* in, int64_t ld_in, int64_
 }
 
 hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
-                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, float* out, int64_t ldo,
-                                bool accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n_cap + 3) / 4)), dim3(256), 0, s, part, ksplit,
-                     part_slice, part_ld, M, rowmap, hdr, out, ldo, accumulate ? 1 : 0);
+                                const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, void* out, int64_t ldo,
+                                bool accumulate, bool out_bf16, hipStream_t s) {
+  const dim3 grid((unsigned)((n_cap + 3) / 4));
+  if (out_bf16)
+    hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, grid, dim3(256), 0, s, part, ksplit, part_slice, part_ld, M,
+                       rowmap, hdr, static_cast<__bf16*>(out), ldo, 0);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, dim3(256), 0, s, part, ksplit, part_slice, part_ld, M,
+                       rowmap, hdr, static_cast<float*>(out), ldo, accumulate ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -366,9 +379,13 @@ hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int6
   return hipGetLastError();
 }
 
-hipError_t launch_zero_padded_rows(float* dH, int d, const int32_t* len, int R, int T, hipStream_t s) {
+hipError_t launch_zero_padded_rows(void* dH, bool bf16, int d, const int32_t* len, int R, int T, hipStream_t s) {
   const int64_t N = (int64_t)R * T;
-  hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s, dH, d, len, R, T);
+  const dim3 grid((unsigned)((N + 3) / 4));
+  if (bf16)
+    hipLaunchKernelGGL(zero_rows_kernel<__bf16>, grid, dim3(256), 0, s, static_cast<__bf16*>(dH), d, len, R, T);
+  else
+    hipLaunchKernelGGL(zero_rows_kernel<float>, grid, dim3(256), 0, s, static_cast<float*>(dH), d, len, R, T);
   return hipGetLastError();
 }
 

@@ -416,12 +416,12 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
     const int r = G::wave() + G::NWAVES * i;
     const int64_t n = n0 + (r / (JG * 32)) * G::WN + p * (JG * 32) + r % (JG * 32);
     int64_t row = -1;
-    if (n < n_lim) row = a.ksplit > 1 ? n : (a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n);
+    if (n < n_lim) row = a.part ? n : (a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n);
     my_row = (int)row;
   }
-  float* const outp = a.ksplit > 1 ? a.part + (size_t)slice * a.part_slice : a.out;
-  const int64_t ldo = a.ksplit > 1 ? a.part_ld : a.ldo;
-  const bool accumulate = a.ksplit > 1 ? false : a.accumulate;
+  float* const outp = a.part ? a.part + (size_t)slice * a.part_slice : a.out;
+  const int64_t ldo = a.part ? a.part_ld : a.ldo;
+  const bool accumulate = a.part ? a.part_accumulate : a.accumulate;
 
   typename G::Acc acc;
   G::zero(acc);

@@ -62,7 +62,8 @@ class GpuProblem:
     def bwd(self, lse, g_logp, dW_init=None):
         import torch
         cfg = self.cfg
-        dH = torch.full((cfg.N, cfg.d), 3.0, dtype=torch.float32, device="cuda")
+        dh_type = torch.bfloat16 if (self.desc.flags & 8) else torch.float32
+        dH = torch.full((cfg.N, cfg.d), 3.0, dtype=dh_type, device="cuda")
         dW = torch.full((cfg.V, cfg.d), 3.0, dtype=torch.float32, device="cuda") if dW_init is None else dW_init
         self.L.lmhead_logprob_bwd(self.desc, self.H, self.W, self.tok, self.lens, lse, g_logp, dH, dW, self.ws)
         return dH, dW

@@ -283,3 +283,24 @@ def test_fp8_logits_variant(vocab_chunk):
     assert bool((logps[0] == logp).all()) and bool((lse2 == lse).all())
     o_ref, _, _ = O.lmhead_logprob_fwd(Hq, O.quantize_e4m3(wl.as_f64(inp["W_ref"]), ew), inp["tok"], inp["lens"], cfg.T)
     assert np.abs(np64(logps[1]) - o_ref).max() <= TOL_LOGP
+
+
+@pytest.mark.parametrize("vocab_chunk", [0, 2048])
+def test_bf16_dh_output_flag(vocab_chunk):
+    """dH written as bf16: the fp32 sums over the vocabulary chunks rounded once at the end."""
+    cfg = wl.CONFIGS[1].scaled(P=2, G=4, T=96, d=256, V=8192 + 100)
+    inp = small_inputs(cfg)
+    g = wl.synthetic_upstream_grad(cfg, inp["lens"])
+    ref = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"], vocab_chunk=vocab_chunk)
+    _, lse, _, _, _ = ref.fwd()
+    dH32, dW32 = ref.bwd(lse, to_device(g))
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"], vocab_chunk=vocab_chunk, flags=8)
+    dH16, dW16 = gp.bwd(lse, to_device(g))
+    assert gp.check() == 0 and dH16.dtype.itemsize == 2
+    assert bool((dW16 == dW32).all())
+    a, b = np64(dH16), np64(dH32)
+    assert np.all(np.abs(a - b) <= 2.0 ** -8 * np.abs(b) + 1e-12)
+    mask = O.index_build(inp["lens"], cfg.T)[0]
+    assert np.all(a[mask == 0] == 0)
+    o_dH, _ = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, g)
+    assert rel_fro(a, o_dH) <= TOL_GRAD

@@ -51,7 +51,7 @@ def test_descriptor_validation_codes(lib):
     assert L.validate_desc(ok) == 0 and L.workspace_bytes(ok) > 0
     cases = [
         (dict(P=0), -2), (dict(T=-1), -2), (dict(V=0), -2), (dict(d=250), -2), (dict(d=0), -2),
-        (dict(ldH=128), -2), (dict(ldW=255), -2), (dict(dtype=7), -3), (dict(flags=1 << 9), -3),
+        (dict(ldH=128), -2), (dict(ldW=255), -2), (dict(dtype=7), -3), (dict(flags=1 << 9), -3), (dict(flags=16), -3),
         (dict(vocab_chunk=-5), -2), (dict(P=70000, G=70000), -2), (dict(ldH=258), -4),
         (dict(fp8_exp_h=3), -2), (dict(fp8_exp_w=-1), -2),                      # exponents without the flag
         (dict(flags=4, d=192, ldH=192, ldW=192), -2), (dict(flags=4, fp8_exp_w=99), -2),
