@@ -277,3 +277,17 @@ def test_append_to_an_existing_store():
     xbar = whole.reconstruct(cache, total, cache_off, k)
     ref = whole.reconstruct(packed_all, total, off_all, k)
     assert whole.check() == 0 and bool((xbar == ref).all())
+
+
+@pytest.mark.parametrize("n,d", [(1, 64), (3, 64), (257, 64), (5, 1024)])
+def test_smallest_streams(n, d):
+    """One token, fewer tokens than a lane group, one token past a tile, the smallest d_kv."""
+    cfg = kv.KV_CONFIGS[0].scaled(n=n, d=d)
+    inp = kv.kv_inputs(cfg)
+    kp, o, (xt, k, m, xhat), same, clear = _gate_parity(cfg, inp, cfg.tau)
+    off, packed = kp.store(xt, k)
+    xbar = kp.reconstruct(packed, int(off[-1].item()), off, k)
+    assert kp.check() == 0
+    assert rel_fro(np64(xbar), o["xbar"]) <= 1e-3
+    out, _ = kp.retain(k, m, 1.0, want_grad=False)
+    assert abs(np64(out)[1] - O.retain_rate_soft(o["m"])) <= 1e-5

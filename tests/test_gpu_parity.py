@@ -304,3 +304,14 @@ def test_bf16_dh_output_flag(vocab_chunk):
     assert np.all(a[mask == 0] == 0)
     o_dH, _ = O.lmhead_logprob_bwd(wl.as_f64(inp["H"]), wl.as_f64(inp["W"]), inp["tok"], inp["lens"], cfg.T, g)
     assert rel_fro(a, o_dH) <= TOL_GRAD
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 64, 5), (1, 2, 3, 64, 257), (3, 1, 7, 128, 256), (1, 1, 300, 64, 1000)])
+def test_smallest_shapes(shape):
+    """Degenerate sizes: one slot, a vocabulary smaller than a tile or exactly one tile, one response,
+    a group of one (advantage 0), a response longer than a token tile."""
+    P, G, T, d, V = shape
+    cfg = wl.CONFIGS[1].scaled(P=P, G=G, T=T, d=d, V=V, len_lo=1, len_hi=T)
+    inp = small_inputs(cfg)
+    r = _grpo_chain(cfg, inp)
+    assert r["o_stats"][3] == inp["lens"].sum()
