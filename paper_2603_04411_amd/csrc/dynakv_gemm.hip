@@ -35,8 +35,19 @@ int compute_units() {
   return cus;
 }
 
+// Tile edge of the KV kernels.  256: one workgroup per compute unit (all of LDS).  128 (build with
+// -DKV_TILE=128): half the LDS and a quarter of the accumulators per workgroup, so two workgroups
+// share a compute unit and one can run its main loop while the other is in its prologue or
+// epilogue, at twice the operand traffic per flop.  Measured on the 262144 x 1024 stream, 128 is
+// 25-40 % slower (714 / 818 / 623 us against 562 / 570 / 500 us for the three kernels), so 256 it is.
+#ifndef KV_TILE
+#define KV_TILE 256
+#endif
+constexpr int kKvTileEdge = KV_TILE;
+constexpr int kKvWgPerCu = kKvTileEdge == 256 ? 1 : 2;
+
 template <typename E, bool kMask>
-using KvTile = GemmTile<E, 256, 256, 2, 2, /*kLeadB=*/true, kMask>;
+using KvTile = GemmTile<E, kKvTileEdge, kKvTileEdge, 2, 2, /*kLeadB=*/true, kMask>;
 
 // One output tile; `wg` is the tile's position in the XCD-aware walk.
 template <typename E, int Mode>
@@ -86,29 +97,40 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   }
 
   // output row of tile column threadIdx.x (fetched now, used after the main loop)
-  int my_row;
-  if constexpr (Mode == 2)
-    my_row = a.order[n0 + threadIdx.x];
-  else
-    my_row = n0 + threadIdx.x < a.Nn ? (int)(n0 + threadIdx.x) : -1;
+  int my_row = -1;
+  if (threadIdx.x < G::BN) {
+    if constexpr (Mode == 2)
+      my_row = a.order[n0 + threadIdx.x];
+    else
+      my_row = n0 + threadIdx.x < a.Nn ? (int)(n0 + threadIdx.x) : -1;
+  }
 
   typename G::Acc acc;
   G::zero(acc);
   G::run_rows(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA, offA, Bbase, offB, limB, bytesB, ksteps,
               smem);
 
-  // The tile leaves through LDS as [n][m] rows of fp32 so that each output row segment is
-  // written by one wavefront instruction (16 bytes per lane for fp32, 8 for bf16).
-  constexpr int JG = 2;
-  constexpr int NCOL = G::WGN * JG * 32;
-  constexpr int P = G::BM * 4 + 16;
+  // The tile leaves through LDS as [n][m] rows of fp32 (as many tile columns per phase as fit) so that
+  // each output row segment is written with 16 bytes per lane for fp32 and 8 for bf16, a whole
+  // number of rows per wavefront instruction.
+  constexpr int JG = G::LDS_BYTES >= G::BN * (G::BM * 4 + 16) + G::BN * 4 ? G::TN : G::TN / 2;
+  constexpr int NPH = G::TN / JG;                 // phases
+  constexpr int NCOL = G::WGN * JG * 32;          // tile columns staged per phase
+  constexpr int P = G::BM * 4 + 16;               // staging row pitch in bytes
+  constexpr int CH = G::BM * 4 / 16;              // lanes per staged row
+  constexpr int RPI = 64 / CH;                    // staged rows per wavefront instruction
+  constexpr int RPW = NCOL / G::NWAVES;           // staged rows per wave and phase
   static_assert(NCOL * P + G::BN * 4 <= G::LDS_BYTES && G::TN % JG == 0, "staging fits in LDS");
-  static_assert(G::BM * 4 / 16 == 64, "one staged row is one wavefront store");
-  static_assert(G::BN == G::NT, "one output row index per thread");
+  static_assert(64 % CH == 0 && RPW % RPI == 0 && RPW * NPH <= 64, "row mapping");
   int* rows_lds = reinterpret_cast<int*>(smem + NCOL * P);
-  rows_lds[threadIdx.x] = my_row;
+  if (threadIdx.x < G::BN) rows_lds[threadIdx.x] = my_row;
+  // staged row -> tile column
+  auto tile_col = [&](int phase, int r) { return (r / (JG * 32)) * G::WN + phase * (JG * 32) + r % (JG * 32); };
+  const int h = G::lane() / CH;                   // which of the instruction's rows this lane works on
+  const int c = G::lane() % CH;                   // its 16-byte chunk of the row = 4 output columns
+  const int m = m0 + c * 4;
 #pragma unroll
-  for (int jg = 0; jg < G::TN / JG; ++jg) {
+  for (int jg = 0; jg < NPH; ++jg) {
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj) {
       const int j = jg * JG + jj;
@@ -122,29 +144,31 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
         }
     }
     lds_barrier();
-    // The wave streams out staged rows wave, wave + 4, ...  Their output row indices are fetched
-    // once (lane 32 p + i holds the one of iteration i of phase p) and then read with readlane, and
-    // the loop is unrolled in batches whose LDS reads are all issued before the first store, so
-    // that the wave (alone on its SIMD) is not serialised on one LDS round trip per row.
-    constexpr int ROWS_PER_WAVE = NCOL / G::NWAVES;   // per phase
-    static_assert(ROWS_PER_WAVE * (G::TN / JG) == 64, "one output row index per lane");
-    auto tile_col = [&](int phase, int i) {
-      const int r = G::wave() + G::NWAVES * i;
-      return (r / (JG * 32)) * G::WN + phase * (JG * 32) + r % (JG * 32);
-    };
-    if (jg == 0) my_row = rows_lds[tile_col(G::lane() / ROWS_PER_WAVE, G::lane() % ROWS_PER_WAVE)];
-    const int c = G::lane();
-    const int m = m0 + c * 4;
-    constexpr int RB = 8;
+    // Instruction i of a wave streams out the staged rows (wave + NWAVES i) RPI + h.  Their output row
+    // indices are fetched once (lane RPW p + RPI i + h holds the one of phase p) and read back with
+    // readlane, and the loop is unrolled in batches whose LDS reads are all issued before the first
+    // store, so that a wave is not serialised on one LDS round trip per row.
+    if (jg == 0) {
+      const int l = G::lane();
+      const int ph = l / RPW, idx = l % RPW;
+      const int r = (G::wave() + G::NWAVES * (idx / RPI)) * RPI + idx % RPI;
+      my_row = ph < NPH ? rows_lds[tile_col(ph, r)] : -1;
+    }
+    constexpr int IPW = RPW / RPI;                // instructions per wave and phase
+    constexpr int RB = IPW < 8 ? IPW : 8;
 #pragma unroll
-    for (int i0 = 0; i0 < ROWS_PER_WAVE; i0 += RB) {
+    for (int i0 = 0; i0 < IPW; i0 += RB) {
       f32x4_t v[RB];
 #pragma unroll
       for (int u = 0; u < RB; ++u)
-        v[u] = *reinterpret_cast<const f32x4_t*>(smem + (G::wave() + G::NWAVES * (i0 + u)) * P + c * 16);
+        v[u] = *reinterpret_cast<const f32x4_t*>(smem + ((G::wave() + G::NWAVES * (i0 + u)) * RPI + h) * P + c * 16);
 #pragma unroll
       for (int u = 0; u < RB; ++u) {
-        const int64_t row = __builtin_amdgcn_readlane(my_row, jg * ROWS_PER_WAVE + i0 + u);
+        int64_t row = __builtin_amdgcn_readlane(my_row, jg * RPW + (i0 + u) * RPI);
+        if constexpr (RPI == 2) {
+          const int r1 = __builtin_amdgcn_readlane(my_row, jg * RPW + (i0 + u) * RPI + 1);
+          row = h ? r1 : row;
+        }
         if (row < 0 || m >= a.M) continue;
         if (a.out_f) {
           *reinterpret_cast<f32x4_t*>(a.out_f + row * a.ldo + m) = v[u];
@@ -152,8 +176,8 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
           *reinterpret_cast<f32x4_t*>(static_cast<float*>(a.out_e) + row * a.ldo + m) = v[u];
         } else {
           typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-          const bf16x4_t h = {(__bf16)v[u].x, (__bf16)v[u].y, (__bf16)v[u].z, (__bf16)v[u].w};
-          *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = h;
+          const bf16x4_t hb = {(__bf16)v[u].x, (__bf16)v[u].y, (__bf16)v[u].z, (__bf16)v[u].w};
+          *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = hb;
         }
       }
     }
@@ -161,10 +185,9 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   }
 }
 
-// Tiles here are short (d_kv / 64 K-steps or fewer), so the workgroups are persistent: one per
-// compute unit, each taking every gridDim.x-th tile of the walk, which saves a workgroup launch
-// (with all of LDS to hand over) per tile.  gridDim.x is a multiple of 8, so a tile stays on the
-// XCD that the walk meant it for.
+// Tiles here are short (d_kv / 64 K-steps or fewer), so the workgroups are persistent: as many as
+// are resident at a time, each taking every gridDim.x-th tile of the walk, which saves a workgroup
+// launch per tile.  gridDim.x is a multiple of 8, so a tile stays on the XCD that the walk meant it for.
 template <typename E, int Mode>
 __global__ __launch_bounds__(256) void kv_gemm_kernel(KvGemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -178,7 +201,7 @@ hipError_t launch_mode(const KvGemmArgs& a, hipStream_t s) {
   const int64_t ntiles = (a.Nn + G::BN - 1) / G::BN;
   KvGemmArgs b = a;
   b.walk_len = (int)xcd_grid_size(mtiles, ntiles, kKvMapBy);
-  const unsigned resident = (unsigned)compute_units() / kNumXcd * kNumXcd;   // one workgroup per CU (LDS-bound)
+  const unsigned resident = (unsigned)compute_units() / kNumXcd * kNumXcd * kKvWgPerCu;   // LDS-bound
   const dim3 grid(b.walk_len < (int)resident ? (unsigned)b.walk_len : resident);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_gemm_kernel<E, Mode>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
