@@ -138,3 +138,39 @@ def retain_penalty(m, alpha: float):
     m = np.asarray(m, dtype=np.float64)
     R = retain_rate_soft(m)
     return alpha * R * R, R, np.full_like(m, 2.0 * alpha * R / max(m.size, 1))
+
+
+def gate_bwd(x, U, W, b, g_xhat, g_m=None, order: str = "suffix"):
+    """Gradients of a scalar L through the training-time gate (Eqs. 1, 5, 6, 7), given
+    ``g_xhat = dL/dx^`` and optionally a direct ``g_m = dL/dm`` (e.g. the retain-rate regulariser's).
+
+    With ``x~ = xU``, ``l = x~W + b``, ``p = softmax(l)``, ``m`` the cumulative mask and ``x^ = x~ * m``:
+        q   = dL/dm   = g_xhat * x~ + g_m
+        r   = dL/dp:   r_j = sum_{i <= j} q_i            (suffix mask: p_j feeds m_0 .. m_j)
+                       r_j = sum_{i <= d-1-j} q_i        (mask as printed in Eq. 6)
+        g_l = dL/dl   = p * (r - sum_k p_k r_k)           (softmax Jacobian)
+        g_xt = dL/dx~ = g_xhat * m + g_l W^T
+        dW = x~^T g_l,  db = sum_tokens g_l,  dU = x^T g_xt,  dx = g_xt U^T.
+    The storage rounding of x~ is treated as the identity (straight-through).  The paper states the
+    forward only ("differentiable gate"); this backward is its plain chain rule: for the paper it is
+    parity unpinned, and it is pinned by finite differences and identities in the tests.
+    Returns dict(dx, dU, dW, db, g_l, g_xt).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    g_xhat = np.asarray(g_xhat, dtype=np.float64)
+    xt = spectral(x, U)
+    p = gate_probs(xt, W, b)
+    m = soft_mask(p, order)
+    q = g_xhat * xt
+    if g_m is not None:
+        q = q + np.asarray(g_m, dtype=np.float64)
+    d = x.shape[1]
+    pre = np.zeros_like(q)
+    for j in range(d):
+        pre[:, j] = q[:, : j + 1].sum(axis=1)
+    r = pre if order == "suffix" else pre[:, ::-1]
+    g_l = p * (r - (p * r).sum(axis=1, keepdims=True))
+    g_xt = g_xhat * m + g_l @ W.T
+    return dict(dx=g_xt @ U.T, dU=x.T @ g_xt, dW=xt.T @ g_l, db=g_l.sum(axis=0), g_l=g_l, g_xt=g_xt)

@@ -207,3 +207,50 @@ def test_synthetic_workload_is_token_adaptive():
     assert 0.25 < R < 0.7 and g["k"].std() > 0.03 * cfg.d           # cut-offs differ token by token
     e = (g["xt"] ** 2).sum(0)
     assert e[: cfg.d // 4].sum() > 0.6 * e.sum()                    # energy sits in the leading components
+
+
+@pytest.mark.parametrize("order", ["suffix", "literal"])
+def test_gate_backward_matches_finite_differences(order):
+    n, d = 4, 6
+    x, U, W, b = _rand(40, n, d), _rand(41, d, d), 0.7 * _rand(42, d, d), _rand(43, d)
+    G, Gm = _rand(44, n, d), _rand(45, n, d)
+
+    def loss(x, U, W, b):
+        g = O.gate(x, U, W, b, 0.1, order=order)
+        return float((G * g["xhat"]).sum() + (Gm * g["m"]).sum())
+
+    got = O.gate_bwd(x, U, W, b, G, Gm, order=order)
+    h = 1e-6
+    for name, arr, key in (("x", x, "dx"), ("U", U, "dU"), ("W", W, "dW"), ("b", b, "db")):
+        fd = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += h
+            lo[idx] -= h
+            args = {"x": x, "U": U, "W": W, "b": b}
+            fd[idx] = (loss(**{**args, name: hi}) - loss(**{**args, name: lo})) / (2 * h)
+        assert np.abs(fd - got[key]).max() <= 1e-6 * max(1.0, np.abs(fd).max()), name
+
+
+def test_gate_backward_identities():
+    n, d = 7, 9
+    x, U, W, b = _rand(46, n, d), _rand(47, d, d), _rand(48, d, d), _rand(49, d)
+    G = _rand(50, n, d)
+    got = O.gate_bwd(x, U, W, b, G)
+    assert np.abs(got["g_l"].sum(axis=1)).max() < 1e-13             # softmax Jacobian annihilates constants
+    assert np.allclose(got["db"], got["g_l"].sum(axis=0))
+    # a mask gradient that is constant over a token's positions and over tokens, c, adds c * (j + 1) to
+    # dL/dp_j: the regulariser of Eq. 9 pushes probability mass towards early cut-offs
+    c = 0.37
+    plus = O.gate_bwd(x, U, W, b, G, np.full((n, d), c))
+    p = O.gate_probs(x @ U, W, b)
+    r = c * (np.arange(d) + 1.0)
+    extra = p * (r - (p * r).sum(axis=1, keepdims=True))
+    assert np.allclose(plus["g_l"] - got["g_l"], extra, atol=1e-12)
+    # with no gate dependence (W = 0) only the direct path x^ = x~ * m remains for x and U, and W's
+    # gradient still sees the mask
+    z = O.gate_bwd(x, U, 0 * W, b, G)
+    m = O.soft_mask(O.gate_probs(x @ U, 0 * W, b))
+    assert np.allclose(z["dx"], (G * m) @ U.T, atol=1e-12) and np.allclose(z["dU"], x.T @ (G * m), atol=1e-12)
