@@ -44,7 +44,8 @@ extern "C" {
 #endif
 
 enum {
-  DYNAKV_FLAG_LITERAL_FLIP = 1u << 0 /* Eq. 6 as printed instead of the reverse cumulative sum */
+  DYNAKV_FLAG_LITERAL_FLIP = 1u << 0, /* Eq. 6 as printed instead of the reverse cumulative sum */
+  DYNAKV_FLAG_ACCUM_GRAD = 1u << 1    /* dynakv_gate_bwd adds to dU, dW, db instead of overwriting them */
 };
 
 enum { DYNAKV_GRANULE = 8 }; /* elements; segment offsets in the store are multiples of this */
@@ -127,6 +128,34 @@ LMHEAD_API int dynakv_reconstruct(const dynakv_desc* desc, const void* packed, i
  */
 LMHEAD_API int dynakv_retain(const dynakv_desc* desc, const int32_t* k, const float* m, float alpha,
                              float* out, float* g_m, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the training-time gate: the chain rule through Eqs. 1, 5, 6 and 7 (the paper trains U, W
+ * and b through this "differentiable gate" with the objective of Eq. 9 and states the forward pass only).
+ * Given g_xhat = dL/dx^ and, optionally, a direct gradient on the soft mask (the regulariser's is the
+ * constant 2 alpha R / (n d): pass it as g_m_const), per token, with p and m recomputed from x~:
+ *     q    = dL/dm      = g_xhat * x~ + g_m + g_m_const
+ *     r_j  = dL/dp_j    = sum_{i <= j} q_i             (p_j feeds m_0 .. m_j;
+ *                                                       sum_{i <= d-1-j} q_i with DYNAKV_FLAG_LITERAL_FLIP)
+ *     g_l  = dL/dlogits = p * (r - sum_j p_j r_j)       fp32, then rounded to the storage type
+ *     g_x~ = dL/dx~     = g_xhat * m + g_l W^T          storage type (the rounding of x~ is passed
+ *                                                       straight through)
+ *     dx = g_x~ U^T,    dU = x^T g_x~,    dW = x~^T g_l,    db = sum over tokens of g_l.
+ *   x      [n x d] row stride ldx (in)     U, W [d x d] (in)     b float[d] (in)
+ *   xt     [n x d] storage type   (in)     x~ as written by dynakv_gate for the same x, U
+ *   g_xhat [n x d] storage type   (in)
+ *   g_m    float[n x d] or NULL   (in)     g_m_const: added to every element of dL/dm
+ *   dx     [n x d] storage type, dense (out)
+ *   dU, dW float[d x d]; db float[d]  (out; added to with DYNAKV_FLAG_ACCUM_GRAD)
+ *   ws     dynakv_bwd_workspace_bytes(desc) bytes (larger than the forward's: it holds the logits, the
+ *          two token-major gradients and token-contiguous copies of the operands of dW and dU)
+ * The contractions over the tokens accumulate in fp32, in slices summed in a fixed order.
+ */
+LMHEAD_API size_t dynakv_bwd_workspace_bytes(const dynakv_desc* desc);
+LMHEAD_API int dynakv_gate_bwd(const dynakv_desc* desc, const void* x, const void* U, const void* W,
+                               const float* b, const void* xt, const void* g_xhat, const float* g_m,
+                               float g_m_const, void* dx, float* dU, float* dW, float* db, void* ws,
+                               size_t ws_bytes, void* stream);
 
 /* Synchronises `stream` and returns LMHEAD_E_RANGE if the most recent dynakv_* call that used
  * `ws` met a device-side range fault (see dynakv_store / dynakv_reconstruct), else LMHEAD_OK

@@ -227,7 +227,8 @@ LMHEAD_API int lmhead_check(void* ws, void* stream);
  * pairs; launches beyond it are not timed) and clears earlier records; (0) turns it off.
  * lmhead_timing_read waits for the recorded events and returns, for one kernel kind
  * (0 = logits forward, 1 = dZ recompute, 2 = dH contraction, 3 = dW contraction, 4 = spectral
- * projection, 5 = gate logits, 6 = truncation mask, 7 = low-rank reconstruction), the summed
+ * projection, 5 = gate logits, 6 = truncation mask, 7 = low-rank reconstruction; of dynakv_gate_bwd:
+ * 8 = mask backward, 9 = g_x~ product, 10 = dx product, 11 = dW, 12 = dU, 13 = operand transposes), the summed
  * elapsed milliseconds and the number of launches since the last enable call.
  */
 LMHEAD_API int lmhead_timing_enable(int on);

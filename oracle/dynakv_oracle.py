@@ -140,7 +140,7 @@ def retain_penalty(m, alpha: float):
     return alpha * R * R, R, np.full_like(m, 2.0 * alpha * R / max(m.size, 1))
 
 
-def gate_bwd(x, U, W, b, g_xhat, g_m=None, order: str = "suffix"):
+def gate_bwd(x, U, W, b, g_xhat, g_m=None, order: str = "suffix", store_dtype=None):
     """Gradients of a scalar L through the training-time gate (Eqs. 1, 5, 6, 7), given
     ``g_xhat = dL/dx^`` and optionally a direct ``g_m = dL/dm`` (e.g. the retain-rate regulariser's).
 
@@ -151,16 +151,18 @@ def gate_bwd(x, U, W, b, g_xhat, g_m=None, order: str = "suffix"):
         g_l = dL/dl   = p * (r - sum_k p_k r_k)           (softmax Jacobian)
         g_xt = dL/dx~ = g_xhat * m + g_l W^T
         dW = x~^T g_l,  db = sum_tokens g_l,  dU = x^T g_xt,  dx = g_xt U^T.
-    The storage rounding of x~ is treated as the identity (straight-through).  The paper states the
-    forward only ("differentiable gate"); this backward is its plain chain rule: for the paper it is
-    parity unpinned, and it is pinned by finite differences and identities in the tests.
+    With ``store_dtype`` the forward quantities (x~, p, m) are those of ``gate``: x~ rounded to the
+    storage type, and that rounding is treated as the identity in the chain rule (straight-through);
+    nothing else is rounded.  The paper gives the forward pass only and calls the gate differentiable;
+    this is the plain chain rule through it, pinned in the tests by central differences of the forward
+    functions above (themselves pinned to the equations) and by identities.
     Returns dict(dx, dU, dW, db, g_l, g_xt).
     """
     x = np.asarray(x, dtype=np.float64)
     U = np.asarray(U, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
     g_xhat = np.asarray(g_xhat, dtype=np.float64)
-    xt = spectral(x, U)
+    xt = round_to(spectral(x, U), store_dtype)
     p = gate_probs(xt, W, b)
     m = soft_mask(p, order)
     q = g_xhat * xt

@@ -39,12 +39,17 @@ from .dynakv import (
     dynakv_reconstruct,
     dynakv_retain,
     dynakv_check,
+    dynakv_bwd_workspace_bytes,
+    dynakv_gate_bwd,
+    FLAG_LITERAL_FLIP,
+    FLAG_ACCUM_GRAD,
     DYNAKV_SYMBOLS,
 )
 
 __all__ = [
     "DynakvDesc", "make_kv_desc", "dynakv_workspace_bytes", "dynakv_validate_desc", "dynakv_gate",
     "dynakv_store", "dynakv_reconstruct", "dynakv_retain", "dynakv_check", "DYNAKV_SYMBOLS",
+    "dynakv_bwd_workspace_bytes", "dynakv_gate_bwd", "FLAG_LITERAL_FLIP", "FLAG_ACCUM_GRAD",
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_fwd_multi", "multi_workspace_bytes", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",

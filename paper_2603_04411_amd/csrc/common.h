@@ -233,7 +233,8 @@ struct GemmTArgs {
 hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
                                 const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, void* out, int64_t ldo,
                                 bool accumulate, bool out_bf16, hipStream_t s);
-hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s);
+// role: -1 = by use (dW when k_from_nv, else dH); 2 = parameter gradient of the KV gate (distinct kernel name).
+hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s, int role = -1);
 
 // Rows of dH that belong to padded slots are set to 0.
 hipError_t launch_zero_padded_rows(void* dH, bool bf16, int d, const int32_t* len, int R, int T,
@@ -257,8 +258,9 @@ constexpr int kLossSlotsPerBlock = 2048;
 // When enabled, each MFMA kernel launch is bracketed by two HIP events recorded on the launch
 // stream.  The pool is fixed-size; launches beyond it are simply not timed.
 // Kinds: 0 logits fwd, 1 dZ recompute, 2 dH, 3 dW, 4 spectral projection, 5 gate logits,
-// 6 truncation mask, 7 low-rank reconstruction.
-constexpr int kTimingKinds = 8;
+// 6 truncation mask, 7 low-rank reconstruction; gate backward: 8 mask backward, 9 g_x~ product, 10 dx
+// product, 11 dW, 12 dU, 13 operand transposes.
+constexpr int kTimingKinds = 14;
 constexpr int kTimingPool = 8192;
 struct TimingState {
   bool on = false;

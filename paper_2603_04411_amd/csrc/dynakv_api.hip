@@ -13,7 +13,7 @@ int validate(const dynakv_desc* d) {
   if (!d) return LMHEAD_E_NULL;
   if (d->n <= 0 || d->d <= 0 || d->d > kKvMaxD || d->d % 64 != 0) return LMHEAD_E_SHAPE;
   if (d->dtype != LMHEAD_F32 && d->dtype != LMHEAD_BF16) return LMHEAD_E_DTYPE;
-  if (d->flags & ~(uint32_t)DYNAKV_FLAG_LITERAL_FLIP) return LMHEAD_E_DTYPE;
+  if (d->flags & ~(uint32_t)(DYNAKV_FLAG_LITERAL_FLIP | DYNAKV_FLAG_ACCUM_GRAD)) return LMHEAD_E_DTYPE;
   if (d->reserved != 0 || d->ldx < d->d) return LMHEAD_E_SHAPE;
   const int64_t esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
   if ((int64_t)d->n * d->d * esz > ((int64_t)1 << 31) - ((int64_t)1 << 20)) return LMHEAD_E_SHAPE;
@@ -177,6 +177,121 @@ int dynakv_retain(const dynakv_desc* desc, const int32_t* k, const float* m, flo
   hipStream_t s = static_cast<hipStream_t>(stream);
   LM_TRY(launch_kv_clear_header(w.at<WsHeader>(L.hdr), s));
   LM_TRY(launch_kv_retain(k, m, L.n, desc->d, alpha, out, g_m, w.at<double>(L.red), s));
+  return LMHEAD_OK;
+}
+
+size_t dynakv_bwd_workspace_bytes(const dynakv_desc* desc) {
+  if (validate(desc) != LMHEAD_OK) return 0;
+  return make_kv_bwd_layout(desc).total;
+}
+
+int dynakv_gate_bwd(const dynakv_desc* desc, const void* x, const void* U, const void* W, const float* b,
+                    const void* xt, const void* g_xhat, const float* g_m, float g_m_const, void* dx, float* dU,
+                    float* dW, float* db, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (!ws || !x || !U || !W || !b || !xt || !g_xhat || !dx || !dU || !dW || !db) return LMHEAD_E_NULL;
+  if (!aligned256(ws)) return LMHEAD_E_ALIGN;
+  if (!aligned16(x) || !aligned16(U) || !aligned16(W) || !aligned16(b) || !aligned16(xt) || !aligned16(g_xhat) ||
+      (g_m && !aligned16(g_m)) || !aligned16(dx) || !aligned16(dU) || !aligned16(dW) || !aligned16(db))
+    return LMHEAD_E_ALIGN;
+  const KvBwdLayout L = make_kv_bwd_layout(desc);
+  if (ws_bytes < L.total) return LMHEAD_E_WORKSPACE;
+  char* const base = static_cast<char*>(ws);
+  auto at = [&](size_t off) { return static_cast<void*>(base + off); };
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WsHeader* hdr = static_cast<WsHeader*>(at(L.hdr));
+  const int dt = desc->dtype;
+  const int d = desc->d;
+  const bool literal = (desc->flags & DYNAKV_FLAG_LITERAL_FLIP) != 0;
+  const bool accum = (desc->flags & DYNAKV_FLAG_ACCUM_GRAD) != 0;
+
+  LM_TRY(launch_kv_clear_header(hdr, s));
+  // parameter operands of the three token-major products: W^T (K-contiguous copy) for the logits, and
+  // row-padded copies of W and U, which are K-contiguous as they are for g_l W^T and g_x~ U^T
+  LM_TRY(launch_transpose(dt, W, d, d, d, false, hdr, at(L.WT), L.ldT, d, L.dp, s));
+  LM_TRY(launch_kv_pad_copy(dt, W, d, d, d, at(L.Wp), L.ldT, (int)L.dp, s));
+  LM_TRY(launch_kv_pad_copy(dt, U, d, d, d, at(L.Up), L.ldT, (int)L.dp, s));
+
+  KvGemmArgs ga{};
+  ga.mode = 1;
+  ga.A = at(L.WT);
+  ga.ldA = L.ldT;
+  ga.B = xt;
+  ga.ldB = d;
+  ga.M = d;
+  ga.Nn = L.n;
+  ga.K = d;
+  ga.out_f = static_cast<float*>(at(L.logits));
+  ga.ldo = d;
+  ga.hdr = hdr;
+  {
+    TimedLaunch tl(5, s);
+    LM_TRY(launch_kv_gemm(dt, ga, s));
+  }
+  {
+    // g_l, and the direct part g_xhat * m of dL/dx~ (into the buffer that the next product adds to)
+    TimedLaunch tl(8, s);
+    LM_TRY(launch_kv_mask_bwd(dt, static_cast<const float*>(at(L.logits)), b, xt, g_xhat, g_m, g_m_const, L.n, d,
+                              literal, at(L.gl), at(L.gxt), static_cast<float*>(at(L.dbpart)), L.nblk, s));
+  }
+  LM_TRY(launch_kv_sum_rows(static_cast<const float*>(at(L.dbpart)), L.nblk, d, d, db, accum, s));
+
+  // g_x~ += g_l W^T
+  ga.mode = 0;
+  ga.A = at(L.Wp);
+  ga.B = at(L.gl);
+  ga.out_f = nullptr;
+  ga.out_e = at(L.gxt);
+  ga.accumulate = true;
+  {
+    TimedLaunch tl(9, s);
+    LM_TRY(launch_kv_gemm(dt, ga, s));
+  }
+  // dx = g_x~ U^T
+  ga.A = at(L.Up);
+  ga.B = at(L.gxt);
+  ga.out_e = dx;
+  ga.accumulate = false;
+  {
+    TimedLaunch tl(10, s);
+    LM_TRY(launch_kv_gemm(dt, ga, s));
+  }
+
+  // Parameter gradients: contractions over the tokens, out[row][col] = sum_t B[row][t] A[col][t] with
+  // token-contiguous copies of both operands, cut into ksplit slices of the token range.
+  auto param_grad = [&](const void* rows_src, int64_t ld_rows, const void* cols_src, int kind, float* out) -> int {
+    {
+      TimedLaunch tl(13, s);
+      LM_TRY(launch_transpose(dt, rows_src, ld_rows, L.n, d, false, hdr, at(L.T1), L.ldK, L.ncap, L.dp, s));
+      LM_TRY(launch_transpose(dt, cols_src, d, L.n, d, false, hdr, at(L.T2), L.ldK, L.ncap, L.dp, s));
+    }
+    GemmTArgs ta{};
+    ta.A = at(L.T2);
+    ta.ldA = L.ldK;
+    ta.B = at(L.T1);
+    ta.ldB = L.ldK;
+    ta.M = d;
+    ta.n_limit = d;
+    ta.K = L.ncap;
+    ta.n_tiles_cap = L.dp / kTile;
+    ta.hdr = hdr;
+    ta.ksplit = L.ksplit;
+    ta.part = static_cast<float*>(at(L.part));
+    ta.part_ld = d;
+    ta.part_slice = (int64_t)d * d;
+    {
+      TimedLaunch tl(kind, s);
+      LM_TRY(launch_gemm_t(dt, ta, s, 2));
+    }
+    LM_TRY(launch_kv_sum_rows(ta.part, L.ksplit, ta.part_slice, ta.part_slice, out, accum, s));
+    return LMHEAD_OK;
+  };
+  // dW[k][j] = sum_t x~[t][k] g_l[t][j];  dU[i][k] = sum_t x[t][i] g_x~[t][k]
+  int prc = param_grad(xt, d, at(L.gl), 11, dW);
+  if (prc != LMHEAD_OK) return prc;
+  prc = param_grad(x, desc->ldx, at(L.gxt), 12, dU);
+  if (prc != LMHEAD_OK) return prc;
   return LMHEAD_OK;
 }
 

@@ -186,6 +186,270 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
   if (lane == 0) k_out[tok] = count;
 }
 
+// ---- backward of the truncation mask ---------------------------------------------------------
+//
+// Chain rule through Eqs. 5-7 for one token, in the position order of kv_mask_kernel (position i =
+// component i of x~, x^ and m; gate column j(i) = i, or d-1-i for Eq. 6 as printed):
+//   p_i = softmax of the logits (+ bias),   m_i = sum_{i' >= i} p_i'          (recomputed)
+//   q_i = dL/dm_i  = g_xhat_i * x~_i + g_m_i + g_m_const
+//   r_i = dL/dp_i  = sum_{i' <= i} q_i'                (p_i feeds m_0 .. m_i)
+//   g_l = dL/dlogit at column j(i) = p_i * (r_i - sum_i' p_i' r_i')             (softmax Jacobian)
+//   a_i = g_xhat_i * m_i                               (the direct part of dL/dx~)
+// One wavefront per token, looping over tokens with the grid's stride.  Each wavefront adds its g_l
+// rows into its own strip of LDS (a lane always owns the same positions, so no atomics and a fixed
+// order); the workgroup's four strips are summed at the end into one row of dbpart.
+// NG as in kv_mask_kernel: NG > 0 keeps the row, r and g_xhat in registers; NG == 0 re-reads.
+template <typename T, int NG>
+__global__ __launch_bounds__(256) void kv_mask_bwd_kernel(const float* __restrict__ logits,
+                                                          const float* __restrict__ bias,
+                                                          const T* __restrict__ xt, const T* __restrict__ gxh,
+                                                          const float* __restrict__ gm, float gmc, int64_t n,
+                                                          int d, int literal, T* __restrict__ gl,
+                                                          T* __restrict__ a_out, float* __restrict__ dbpart) {
+  extern __shared__ float colsum[];   // [4][d], position order
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  float* const acc = colsum + wave * d;
+  const int ngroups = NG > 0 ? NG : (d + 255) / 256;
+  for (int g = 0; g < ngroups; ++g) {
+    const int i0 = g * 256 + lane * 4;
+    if (i0 < d) *reinterpret_cast<float4*>(acc + i0) = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  constexpr int NR = NG > 0 ? NG : 1;
+
+  for (int64_t tok = (int64_t)blockIdx.x * 4 + wave; tok < n; tok += (int64_t)gridDim.x * 4) {
+    const float* z = logits + tok * d;
+    auto load4 = [&](int i0, float (&v)[4]) {
+      if (!literal) {
+        const float4 a = *reinterpret_cast<const float4*>(z + i0);
+        const float4 b = *reinterpret_cast<const float4*>(bias + i0);
+        v[0] = a.x + b.x; v[1] = a.y + b.y; v[2] = a.z + b.z; v[3] = a.w + b.w;
+      } else {
+        const int j0 = d - 4 - i0;
+        const float4 a = *reinterpret_cast<const float4*>(z + j0);
+        const float4 b = *reinterpret_cast<const float4*>(bias + j0);
+        v[0] = a.w + b.w; v[1] = a.z + b.z; v[2] = a.y + b.y; v[3] = a.x + b.x;
+      }
+    };
+
+    // softmax statistics, as in the forward kernel
+    float row[NR][4];
+    float mx = -__builtin_huge_valf();
+    float sum = 0.f;
+    if constexpr (NG > 0) {
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int i0 = g * 256 + lane * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) row[g][e] = -__builtin_huge_valf();
+        if (i0 < d) load4(i0, row[g]);
+      }
+#pragma unroll
+      for (int g = 0; g < NG; ++g) mx = fmaxf(fmaxf(mx, fmaxf(row[g][0], row[g][1])), fmaxf(row[g][2], row[g][3]));
+      mx = wave_max(mx);
+#pragma unroll
+      for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          row[g][e] = __builtin_amdgcn_exp2f((row[g][e] - mx) * kLog2e);
+          sum += row[g][e];
+        }
+    } else {
+      for (int g = 0; g < ngroups; ++g) {
+        const int i0 = g * 256 + lane * 4;
+        if (i0 < d) {
+          float v[4];
+          load4(i0, v);
+          mx = fmaxf(fmaxf(mx, fmaxf(v[0], v[1])), fmaxf(v[2], v[3]));
+        }
+      }
+      mx = wave_max(mx);
+      for (int g = 0; g < ngroups; ++g) {
+        const int i0 = g * 256 + lane * 4;
+        if (i0 < d) {
+          float v[4];
+          load4(i0, v);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+        }
+      }
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+
+    // the lane's four exponentials of group g (0 beyond d)
+    auto expo = [&](int g, float (&s)[4]) {
+      if constexpr (NG > 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] = row[g][e];
+      } else {
+        const int i0 = g * 256 + lane * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] = 0.f;
+        if (i0 < d) {
+          float v[4];
+          load4(i0, v);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[e] = __builtin_amdgcn_exp2f((v[e] - mx) * kLog2e);
+        }
+      }
+    };
+    // q of group g turned into r: the inclusive prefix sums over all positions up to each one
+    auto prefix = [&](int g, float& carry, float (&r)[4], float (&gx)[4]) {
+      const int i0 = g * 256 + lane * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = gx[e] = 0.f;
+      if (i0 < d) {
+        float xv[4];
+        Store4<T>::load(xt + tok * d + i0, xv);
+        Store4<T>::load(gxh + tok * d + i0, gx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = gx[e] * xv[e] + gmc;
+        if (gm) {
+          const float4 t = *reinterpret_cast<const float4*>(gm + tok * d + i0);
+          r[0] += t.x; r[1] += t.y; r[2] += t.z; r[3] += t.w;
+        }
+      }
+      r[1] += r[0];
+      r[2] += r[1];
+      r[3] += r[2];
+      float incl = r[3];
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const float y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+      }
+      const float below = carry + (incl - r[3]);
+      carry += __shfl(incl, 63);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] += below;
+    };
+
+    // r and s = sum_i p_i r_i
+    float rk[NR][4], gxk[NR][4];
+    float s = 0.f;
+    {
+      float carry = 0.f;
+      auto step = [&](int g, float (&r)[4], float (&gx)[4]) {
+        prefix(g, carry, r, gx);
+        float ex[4];
+        expo(g, ex);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += ex[e] * r[e];
+      };
+      if constexpr (NG > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) step(g, rk[g], gxk[g]);
+      } else {
+        for (int g = 0; g < ngroups; ++g) step(g, rk[0], gxk[0]);
+      }
+    }
+    s = wave_sum(s) * inv;
+
+    // m (suffix sums, last group first) and a = g_xhat * m
+    {
+      float carry = 0.f;
+      auto step = [&](int g, const float (&gx_kept)[4]) {
+        const int i0 = g * 256 + lane * 4;
+        float sfx[4];
+        expo(g, sfx);
+        sfx[2] += sfx[3];
+        sfx[1] += sfx[2];
+        sfx[0] += sfx[1];
+        float incl = sfx[0];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const float y = __shfl_down(incl, o);
+          if (lane + o < 64) incl += y;
+        }
+        const float above = carry + (incl - sfx[0]);
+        carry += __shfl(incl, 0);
+        if (i0 < d) {
+          float gx[4];
+          if constexpr (NG > 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gx[e] = gx_kept[e];
+          } else {
+            Store4<T>::load(gxh + tok * d + i0, gx);
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gx[e] *= (above + sfx[e]) * inv;
+          Store4<T>::store(a_out + tok * d + i0, gx);
+        }
+      };
+      if constexpr (NG > 0) {
+#pragma unroll
+        for (int g = NG - 1; g >= 0; --g) step(g, gxk[g]);
+      } else {
+        for (int g = ngroups - 1; g >= 0; --g) step(g, gxk[0]);
+      }
+    }
+
+    // g_l = p (r - s), stored in gate column order and added to the wavefront's column sums
+    {
+      float carry = 0.f;
+      auto step = [&](int g, float (&r)[4]) {
+        const int i0 = g * 256 + lane * 4;
+        if constexpr (NG == 0) {
+          float gx[4];
+          prefix(g, carry, r, gx);
+        }
+        float ex[4];
+        expo(g, ex);
+        if (i0 < d) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = ex[e] * inv * (r[e] - s);
+          float4 t = *reinterpret_cast<const float4*>(acc + i0);
+          t.x += v[0]; t.y += v[1]; t.z += v[2]; t.w += v[3];
+          *reinterpret_cast<float4*>(acc + i0) = t;
+          if (!literal) {
+            Store4<T>::store(gl + tok * d + i0, v);
+          } else {
+            const float w[4] = {v[3], v[2], v[1], v[0]};
+            Store4<T>::store(gl + tok * d + (d - 4 - i0), w);
+          }
+        }
+      };
+      if constexpr (NG > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) step(g, rk[g]);
+      } else {
+        for (int g = 0; g < ngroups; ++g) step(g, rk[0]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float t = ((colsum[c] + colsum[d + c]) + colsum[2 * d + c]) + colsum[3 * d + c];
+    dbpart[(int64_t)blockIdx.x * d + (literal ? d - 1 - c : c)] = t;
+  }
+}
+
+// out[j] (+)= sum over the rows of part, in row order.
+__global__ __launch_bounds__(256) void kv_sum_rows_kernel(const float* __restrict__ part, int rows, int64_t row_pitch,
+                                                          int64_t len, float* __restrict__ out, int accumulate) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= len) return;
+  float t = part[j];
+  for (int r = 1; r < rows; ++r) t += part[r * row_pitch + j];
+  out[j] = accumulate ? out[j] + t : t;
+}
+
+// Row-padded copy of a parameter matrix: 16 bytes per thread, zero beyond the source's extent.
+__global__ __launch_bounds__(256) void kv_pad_copy_kernel(const char* __restrict__ in, int64_t in_pitch, int rows,
+                                                          int row_bytes, char* __restrict__ out, int64_t out_pitch,
+                                                          int rows_p) {
+  const int chunks = (int)(out_pitch / 16);
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t r = id / chunks;
+  const int c = (int)(id % chunks) * 16;
+  if (r >= rows_p) return;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (r < rows && c < row_bytes) v = *reinterpret_cast<const uint4*>(in + r * in_pitch + c);
+  *reinterpret_cast<uint4*>(out + r * out_pitch + c) = v;
+}
+
 // ---- ragged store ---------------------------------------------------------------------------
 
 __device__ inline int seg_len(int k, int d, int& bad) {
@@ -487,6 +751,64 @@ hipError_t launch_kv_mask(int dtype, const float* logits, const float* b, const 
     launch_mask_t<__bf16>(logits, b, xt, n, d, tau, literal, k, m, xhat, s);
   else
     launch_mask_t<float>(logits, b, xt, n, d, tau, literal, k, m, xhat, s);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_mask_bwd_t(const float* logits, const float* b, const void* xt, const void* g_xhat,
+                                    const float* g_m, float g_m_const, int64_t n, int d, bool literal, void* gl,
+                                    void* a_out, float* dbpart, int nblk, hipStream_t s) {
+  const dim3 grid((unsigned)nblk);
+  const size_t lds = (size_t)4 * d * sizeof(float);
+  const T* x = static_cast<const T*>(xt);
+  const T* gx = static_cast<const T*>(g_xhat);
+  T* g1 = static_cast<T*>(gl);
+  T* a1 = static_cast<T*>(a_out);
+  const int lit = literal ? 1 : 0;
+  const int ng = (d + 255) / 256;
+#define KV_MASK_BWD(NG)                                                                                          \
+  do {                                                                                                           \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_mask_bwd_kernel<T, NG>),                 \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                    \
+    if (e != hipSuccess) return e;                                                                               \
+    hipLaunchKernelGGL((kv_mask_bwd_kernel<T, NG>), grid, dim3(256), lds, s, logits, b, x, gx, g_m, g_m_const, n, \
+                       d, lit, g1, a1, dbpart);                                                                  \
+  } while (0)
+  switch (ng) {
+    case 1: KV_MASK_BWD(1); break;
+    case 2: KV_MASK_BWD(2); break;
+    case 3: KV_MASK_BWD(3); break;
+    case 4: KV_MASK_BWD(4); break;
+    case 5: case 6: KV_MASK_BWD(6); break;
+    case 7: case 8: KV_MASK_BWD(8); break;
+    default: KV_MASK_BWD(0); break;
+  }
+#undef KV_MASK_BWD
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_mask_bwd(int dtype, const float* logits, const float* b, const void* xt, const void* g_xhat,
+                              const float* g_m, float g_m_const, int64_t n, int d, bool literal, void* gl,
+                              void* a_out, float* dbpart, int nblk, hipStream_t s) {
+  if (dtype == LMHEAD_BF16)
+    return launch_mask_bwd_t<__bf16>(logits, b, xt, g_xhat, g_m, g_m_const, n, d, literal, gl, a_out, dbpart, nblk, s);
+  return launch_mask_bwd_t<float>(logits, b, xt, g_xhat, g_m, g_m_const, n, d, literal, gl, a_out, dbpart, nblk, s);
+}
+
+hipError_t launch_kv_sum_rows(const float* part, int rows, int64_t row_pitch, int64_t len, float* out,
+                              bool accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(kv_sum_rows_kernel, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, s, part, rows, row_pitch,
+                     len, out, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_pad_copy(int dtype, const void* in, int64_t ld_in, int rows, int cols, void* out,
+                              int64_t ld_out, int rows_p, hipStream_t s) {
+  const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
+  const int64_t threads = (int64_t)rows_p * (ld_out * esz / 16);
+  hipLaunchKernelGGL(kv_pad_copy_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                     static_cast<const char*>(in), ld_in * esz, rows, cols * esz, static_cast<char*>(out),
+                     ld_out * esz, rows_p);
   return hipGetLastError();
 }
 

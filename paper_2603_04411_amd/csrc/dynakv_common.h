@@ -53,6 +53,64 @@ static inline KvLayout make_kv_layout(const dynakv_desc* d) {
   return L;
 }
 
+// Workspace of the gate's backward pass (dynakv_gate_bwd).  The two token-major gradients g_l and
+// g_xt are kept in the storage type; T1 / T2 hold the token-contiguous (transposed) operand copies of
+// one parameter-gradient contraction at a time.
+struct KvBwdLayout {
+  int esz;
+  int64_t n, d, ncap, dp, ldT;
+  int64_t ldK;       // pitch (elements) of the token-contiguous copies: ncap + one 128-byte line
+  int ksplit;        // slices of the contraction over tokens per output tile of dW / dU
+  int nblk;          // workgroups of the mask backward kernel = rows of the db partial sums
+  size_t hdr, Wp, Up, WT, logits, gl, gxt, T1, T2, part, dbpart, total;
+};
+
+constexpr int kKvBwdMaxBlocks = 2048;
+
+static inline KvBwdLayout make_kv_bwd_layout(const dynakv_desc* d) {
+  KvBwdLayout L{};
+  L.esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
+  L.n = d->n;
+  L.d = d->d;
+  L.ncap = (int64_t)round_up((size_t)L.n, kTile);
+  L.dp = (int64_t)round_up((size_t)L.d, kTile);
+  L.ldT = L.d + 128 / L.esz;
+  L.ldK = L.ncap + 128 / L.esz;
+  {
+    // (d / 256)^2 output tiles; the contraction over the tokens is cut so that about one workgroup
+    // per compute unit runs, each slice keeping at least 8 K-steps
+    const int64_t tiles = (L.dp / kTile) * (L.dp / kTile);
+    const int64_t ksteps = L.ncap * L.esz / 128;
+    int64_t ks = (256 + tiles - 1) / tiles;
+    if (ks > ksteps / 8) ks = ksteps / 8;
+    if (ks < 1) ks = 1;
+    L.ksplit = (int)ks;
+  }
+  {
+    const int64_t blocks = (L.n + 3) / 4;
+    L.nblk = (int)(blocks < kKvBwdMaxBlocks ? blocks : kKvBwdMaxBlocks);
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return o;
+  };
+  L.hdr = take(sizeof(WsHeader));
+  L.Wp = take((size_t)L.dp * L.ldT * L.esz);
+  L.Up = take((size_t)L.dp * L.ldT * L.esz);
+  L.WT = take((size_t)L.dp * L.ldT * L.esz);
+  L.logits = take((size_t)L.ncap * L.d * 4);
+  L.gl = take((size_t)L.ncap * L.d * L.esz);
+  L.gxt = take((size_t)L.ncap * L.d * L.esz);
+  L.T1 = take((size_t)L.dp * L.ldK * L.esz);
+  L.T2 = take((size_t)L.dp * L.ldK * L.esz);
+  L.part = take((size_t)L.ksplit * L.d * L.d * 4);
+  L.dbpart = take((size_t)L.nblk * L.d * 4);
+  L.total = off;
+  return L;
+}
+
 // Plain contraction on the MFMA tile core with a transposed store:
 //   out[row(n)][m] = sum_k A[m][k] * Bop[n][k],  m < M, n < Nn.
 // mode 0/1: Bop rows are dense rows of B (pitch ldB), row(n) = n.  The output is the storage type
@@ -76,6 +134,7 @@ struct KvGemmArgs {
   void* out_e;
   float* out_f;
   int64_t ldo;
+  bool accumulate;      // mode 0/1: the tile is added to what the output holds (rounded once more for bf16)
   WsHeader* hdr;
   int walk_len;         // set by the launcher: length of the tile walk (tile_map.h)
 };
@@ -102,6 +161,23 @@ hipError_t launch_kv_order(int dtype, const int32_t* k, const int64_t* off, int6
 
 hipError_t launch_kv_retain(const int32_t* k, const float* m, int64_t n, int d, float alpha, float* out,
                             float* g_m, double* red, hipStream_t s);
+
+// Backward of softmax + cumulative mask + soft gating for every token (one wavefront per token):
+//   q = g_xhat * xt + g_m + g_m_const;  r = inclusive prefix sums of q;  g_l = p * (r - sum p r);
+//   a = g_xhat * m.
+// g_l goes to gl (gate column order) and a to a_out, both [n x d] in the storage type; dbpart
+// receives one row of column sums of g_l per workgroup (nblk rows, launch grid = nblk).
+hipError_t launch_kv_mask_bwd(int dtype, const float* logits, const float* b, const void* xt, const void* g_xhat,
+                              const float* g_m, float g_m_const, int64_t n, int d, bool literal, void* gl,
+                              void* a_out, float* dbpart, int nblk, hipStream_t s);
+
+// out[j] (+)= sum_r part[r][j] for j < len, rows (pitch row_pitch floats) summed in order.
+hipError_t launch_kv_sum_rows(const float* part, int rows, int64_t row_pitch, int64_t len, float* out,
+                              bool accumulate, hipStream_t s);
+
+// out[r][c] = in[r][c] for r < rows, c < cols; zero up to [rows_p x ld_out].
+hipError_t launch_kv_pad_copy(int dtype, const void* in, int64_t ld_in, int rows, int cols, void* out,
+                              int64_t ld_out, int rows_p, hipStream_t s);
 
 hipError_t launch_kv_clear_header(WsHeader* hdr, hipStream_t s);
 

@@ -1,5 +1,6 @@
 // Matrix-core kernels of the KV-compression path, built on GemmTile (gemm_core.h):
-//   mode 0  spectral projection     x~ = x U                      (Eq. 1)
+//   mode 0  spectral projection     x~ = x U                      (Eq. 1); also the two token-major
+//           products of the gate's backward pass, optionally added to what the output holds
 //   mode 1  gate logits             x~ W          (fp32, bias added by the mask kernel; Eq. 5)
 //   mode 2  dynamic low-rank reconstruction  x_bar = x^[0:k] U^-1[0:k, :]   (Eq. 3)
 // All three are  out[row(n)][m] = sum_k A[m][k] Bop[n][k]  with the parameter matrix (transposed
@@ -45,6 +46,8 @@ int compute_units() {
 #endif
 constexpr int kKvTileEdge = KV_TILE;
 constexpr int kKvWgPerCu = kKvTileEdge == 256 ? 1 : 2;
+
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 
 template <typename E, bool kMask>
 using KvTile = GemmTile<E, kKvTileEdge, kKvTileEdge, 2, 2, /*kLeadB=*/true, kMask>;
@@ -159,6 +162,7 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
 #pragma unroll
     for (int i0 = 0; i0 < IPW; i0 += RB) {
       f32x4_t v[RB];
+      int64_t orow[RB];
 #pragma unroll
       for (int u = 0; u < RB; ++u)
         v[u] = *reinterpret_cast<const f32x4_t*>(smem + ((G::wave() + G::NWAVES * (i0 + u)) * RPI + h) * P + c * 16);
@@ -169,13 +173,38 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
           const int r1 = __builtin_amdgcn_readlane(my_row, jg * RPW + (i0 + u) * RPI + 1);
           row = h ? r1 : row;
         }
-        if (row < 0 || m >= a.M) continue;
+        orow[u] = m < a.M ? row : -1;
+      }
+      if constexpr (Mode != 2) {
+        // the batch's old values are all requested before the first of them is used
+        if (a.accumulate) {
+          f32x4_t old[RB];
+#pragma unroll
+          for (int u = 0; u < RB; ++u) {
+            old[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (orow[u] < 0) continue;
+            if (a.out_f) {
+              old[u] = *reinterpret_cast<const f32x4_t*>(a.out_f + orow[u] * a.ldo + m);
+            } else if constexpr (ESZ == 4) {
+              old[u] = *reinterpret_cast<const f32x4_t*>(static_cast<const float*>(a.out_e) + orow[u] * a.ldo + m);
+            } else {
+              const bf16x4_t hb = *reinterpret_cast<const bf16x4_t*>(static_cast<const __bf16*>(a.out_e) + orow[u] * a.ldo + m);
+              old[u] = f32x4_t{(float)hb.x, (float)hb.y, (float)hb.z, (float)hb.w};
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < RB; ++u) v[u] += old[u];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < RB; ++u) {
+        const int64_t row = orow[u];
+        if (row < 0) continue;
         if (a.out_f) {
           *reinterpret_cast<f32x4_t*>(a.out_f + row * a.ldo + m) = v[u];
         } else if constexpr (ESZ == 4) {
           *reinterpret_cast<f32x4_t*>(static_cast<float*>(a.out_e) + row * a.ldo + m) = v[u];
         } else {
-          typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
           const bf16x4_t hb = {(__bf16)v[u].x, (__bf16)v[u].y, (__bf16)v[u].z, (__bf16)v[u].w};
           *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(a.out_e) + row * a.ldo + m) = hb;
         }

@@ -367,8 +367,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   }
 }
 
-// Role: 0 = dH (contracts over a vocabulary chunk), 1 = dW (contracts over the valid tokens).  The
-// code is the same; the parameter only gives the two uses distinct kernel names in profiles.
+// Role: 0 = dH (contracts over a vocabulary chunk), 1 = dW (contracts over the valid tokens), 2 = a
+// parameter gradient of the KV gate (contracts over the tokens of a stream).  The code is the same; the
+// parameter only gives the uses distinct kernel names in profiles (and picks the lead operand).
 template <typename E, int Role>
 __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   using G = Tile<E, (Role == 0 ? kLeadDh : kLeadDw)>;
@@ -527,8 +528,10 @@ static hipError_t launch_gemm_t_impl(const GemmTArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s) {
+hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s, int role) {
   const bool dw = a.k_from_nv;
+  if (role == 2)
+    return dtype == LMHEAD_BF16 ? launch_gemm_t_impl<bf16_tag, 2>(a, s) : launch_gemm_t_impl<f32_tag, 2>(a, s);
   if (dtype == LMHEAD_BF16)
     return dw ? launch_gemm_t_impl<bf16_tag, 1>(a, s) : launch_gemm_t_impl<bf16_tag, 0>(a, s);
   return dw ? launch_gemm_t_impl<f32_tag, 1>(a, s) : launch_gemm_t_impl<f32_tag, 0>(a, s);

@@ -10,10 +10,11 @@ from .binding import LMHEAD_BF16, LMHEAD_F32, _check, _ptr, _stream, load_librar
 
 DYNAKV_SYMBOLS = [
     "dynakv_workspace_bytes", "dynakv_validate_desc", "dynakv_gate", "dynakv_store",
-    "dynakv_reconstruct", "dynakv_retain", "dynakv_check",
+    "dynakv_reconstruct", "dynakv_retain", "dynakv_check", "dynakv_bwd_workspace_bytes", "dynakv_gate_bwd",
 ]
 
 FLAG_LITERAL_FLIP = 1 << 0
+FLAG_ACCUM_GRAD = 1 << 1
 GRANULE = 8
 
 
@@ -45,6 +46,10 @@ def _lib():
         lib.dynakv_reconstruct.argtypes = [dp, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         lib.dynakv_retain.restype = C.c_int
         lib.dynakv_retain.argtypes = [dp, vp, vp, f32, vp, vp, vp, sz, vp]
+        lib.dynakv_bwd_workspace_bytes.restype = sz
+        lib.dynakv_bwd_workspace_bytes.argtypes = [dp]
+        lib.dynakv_gate_bwd.restype = C.c_int
+        lib.dynakv_gate_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
         lib.dynakv_check.restype = C.c_int
         lib.dynakv_check.argtypes = [vp, vp]
         _ready = True
@@ -90,6 +95,17 @@ def dynakv_retain(desc, k, m, alpha, out, g_m, ws) -> None:
     rc = _lib().dynakv_retain(C.byref(desc), _ptr(k), _ptr(m), alpha, _ptr(out), _ptr(g_m), _ptr(ws), _nbytes(ws),
                               _stream())
     _check(rc, "dynakv_retain")
+
+
+def dynakv_bwd_workspace_bytes(desc: DynakvDesc) -> int:
+    return int(_lib().dynakv_bwd_workspace_bytes(C.byref(desc)))
+
+
+def dynakv_gate_bwd(desc, x, U, W, b, xt, g_xhat, g_m, g_m_const, dx, dU, dW, db, ws) -> None:
+    rc = _lib().dynakv_gate_bwd(C.byref(desc), _ptr(x), _ptr(U), _ptr(W), _ptr(b), _ptr(xt), _ptr(g_xhat),
+                                _ptr(g_m), g_m_const, _ptr(dx), _ptr(dU), _ptr(dW), _ptr(db), _ptr(ws),
+                                _nbytes(ws), _stream())
+    _check(rc, "dynakv_gate_bwd")
 
 
 def dynakv_check(ws) -> int:

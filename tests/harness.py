@@ -183,5 +183,27 @@ class KvProblem:
         self.L.dynakv_retain(self.desc, k, m, alpha, out, g, self.ws)
         return out, g
 
+    def gate_bwd(self, xt, g_xhat, g_m=None, g_m_const=0.0, accumulate_into=None):
+        """dx, dU, dW, db of dynakv_gate_bwd (its own, larger workspace).  `accumulate_into` = (dU, dW, db)
+        tensors to add to, with DYNAKV_FLAG_ACCUM_GRAD."""
+        import torch
+        cfg = self.cfg
+        desc = self.desc
+        if accumulate_into is not None:
+            desc = self.L.make_kv_desc(cfg.n, cfg.d, cfg.dtype, ldx=self.desc.ldx,
+                                       flags=self.desc.flags | self.L.FLAG_ACCUM_GRAD)
+        if getattr(self, "ws_bwd", None) is None:
+            self.ws_bwd = torch.empty(self.L.dynakv_bwd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+        dx = torch.full((cfg.n, cfg.d), 3.0, dtype=self.tdt, device="cuda")
+        if accumulate_into is None:
+            dU = torch.full((cfg.d, cfg.d), 3.0, dtype=torch.float32, device="cuda")
+            dW = torch.full((cfg.d, cfg.d), 3.0, dtype=torch.float32, device="cuda")
+            db = torch.full((cfg.d,), 3.0, dtype=torch.float32, device="cuda")
+        else:
+            dU, dW, db = accumulate_into
+        self.L.dynakv_gate_bwd(desc, self.x, self.U, self.W, self.b, xt, g_xhat, g_m, g_m_const, dx, dU, dW, db,
+                               self.ws_bwd)
+        return dx, dU, dW, db
+
     def check(self):
         return self.L.dynakv_check(self.ws)

@@ -114,7 +114,7 @@ def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert c(p, p, 8, 32, p, p, p, 4, None) == -5
     assert lib.lmhead_check(None, None) == -1
     ms, n = C.c_double(), C.c_int64()
-    assert lib.lmhead_timing_read(9, C.byref(ms), C.byref(n)) == -2
+    assert lib.lmhead_timing_read(14, C.byref(ms), C.byref(n)) == -2
     assert lib.lmhead_timing_read(0, None, C.byref(n)) == -1
 
 
@@ -127,7 +127,7 @@ def test_dynakv_descriptor_and_argument_validation(lib):
     assert need > 1000 * 512 * 4        # holds the fp32 gate logits
     cases = [
         (dict(n=0), -2), (dict(d=0), -2), (dict(d=100), -2), (dict(d=16384), -2), (dict(dtype=5), -3),
-        (dict(flags=2), -3), (dict(ldx=256), -2), (dict(ldx=516), -4), (dict(n=1 << 22), -2),
+        (dict(flags=4), -3), (dict(ldx=256), -2), (dict(ldx=516), -4), (dict(n=1 << 22), -2),
     ]
     for change, code in cases:
         kw = dict(n=1000, d=512, dtype="bf16")
@@ -155,6 +155,19 @@ def test_dynakv_descriptor_and_argument_validation(lib):
     assert rec(d, p, 1 << 20, p, p, p, p, p, 100, None) == -5
     assert ret(d, p, p, 0.5, None, None, p, need, None) == -1
     assert ret(d, p, p + 4, 0.5, p, None, p, need, None) == -4
+    # the backward: a workspace of its own size, larger than the forward's
+    bneed = L.dynakv_bwd_workspace_bytes(ok)
+    assert bneed > need + 2 * 1000 * 512 * 2 and L.dynakv_bwd_workspace_bytes(L.make_kv_desc(1000, 100, "bf16")) == 0
+    assert L.dynakv_validate_desc(L.make_kv_desc(1000, 512, "bf16", flags=L.FLAG_ACCUM_GRAD | L.FLAG_LITERAL_FLIP)) == 0
+    bwd = lib.dynakv_gate_bwd
+    bwd.argtypes = [C.c_void_p] * 8 + [C.c_float] + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]
+    bwd.restype = C.c_int
+    assert bwd(d, p, p, p, p, p, None, None, 0.0, p, p, p, p, p, bneed, None) == -1
+    assert bwd(d, p, p, p, p, p, p, None, 0.0, p, p, p, None, p, bneed, None) == -1
+    assert bwd(d, p, p, p, p, p, p, p + 4, 0.0, p, p, p, p, p, bneed, None) == -4
+    assert bwd(d, p, p, p, p, p, p, None, 0.0, p, p, p, p, p + 32, bneed, None) == -4
+    assert bwd(d, p, p, p, p, p, p, None, 0.0, p, p, p, p, p, bneed - 1, None) == -5
+    assert bwd(d, p, p, p, p, p, p, None, 0.0, p, p, p, p, p, need, None) == -5
     assert lib.dynakv_check(None, None) == -1
 
 

@@ -14,6 +14,8 @@ Recipe (stands in for the activations of an 8B model, which are not available of
   * gate: ``W ~ N(0, w_std^2)`` and a bias bump ``b_j = h exp(-(j-c)^2 / (2 s^2))`` centred at
     ``c = 0.35 d`` with ``s = 0.12 d``: cut-off positions vary token by token around the bump.
 All four parameter tensors and ``x`` are rounded to the storage type.
+For the gate's backward pass: upstream gradients ``g_xhat ~ N(0, 1/n)`` (storage type; the scale of
+a mean-reduced loss) and, optionally, ``g_m ~ N(0, 1/n)`` (float32).
 """
 from __future__ import annotations
 
@@ -27,6 +29,8 @@ STREAM_X = 20
 STREAM_Q = 21
 STREAM_U = 22
 STREAM_GATE_W = 23
+STREAM_G_XHAT = 24
+STREAM_G_M = 25
 ROWS_PER_BLOCK = 4096
 
 
@@ -106,3 +110,22 @@ def kv_inputs(cfg: KvWorkload) -> dict:
     u, u_inv = basis(cfg, q)
     w, b = gate_params(cfg)
     return dict(x=states(cfg, q), U=u, U_inv=u_inv, W=w, b=b)
+
+
+def upstream(cfg: KvWorkload, rows: np.ndarray | None = None, with_g_m: bool = False):
+    """(g_xhat stored type [n x d], g_m float32 [n x d] or None).  With `rows`, every other row is 0."""
+    scale = np.float32(1.0 / np.sqrt(cfg.n))
+    g = np.empty((cfg.n, cfg.d), dtype=np.float32)
+    gm = np.empty((cfg.n, cfg.d), dtype=np.float32) if with_g_m else None
+    for blk, r0 in enumerate(range(0, cfg.n, ROWS_PER_BLOCK)):
+        r1 = min(cfg.n, r0 + ROWS_PER_BLOCK)
+        g[r0:r1] = scale * _rng(cfg, STREAM_G_XHAT, blk).standard_normal((r1 - r0, cfg.d), dtype=np.float32)
+        if with_g_m:
+            gm[r0:r1] = scale * _rng(cfg, STREAM_G_M, blk).standard_normal((r1 - r0, cfg.d), dtype=np.float32)
+    if rows is not None:
+        keep = np.zeros(cfg.n, dtype=bool)
+        keep[rows] = True
+        g[~keep] = 0
+        if with_g_m:
+            gm[~keep] = 0
+    return _store(cfg, g), gm
