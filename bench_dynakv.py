@@ -28,6 +28,11 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 KINDS = {4: "kv_gemm_kernel<spectral projection>", 5: "kv_gemm_kernel<gate logits>",
          6: "kv_mask_kernel (softmax + cumulative mask + threshold)", 7: "kv_gemm_kernel<reconstruction>"}
+# --backward: one step = dynakv_gate (training outputs off) + dynakv_gate_bwd
+BWD_KINDS = {4: "kv_gemm_kernel<spectral projection>", 5: "kv_gemm_kernel<gate logits> (forward + recompute)",
+             6: "kv_mask_kernel", 8: "kv_mask_bwd_kernel", 9: "kv_gemm_kernel<g_x~ = g_l W^T + g_xhat m>",
+             10: "kv_gemm_kernel<dx = g_x~ U^T>", 11: "gemm_t_kernel<dW>", 12: "gemm_t_kernel<dU>",
+             13: "transpose_kernel (two operand copies per parameter gradient)"}
 
 
 TRAFFIC_KEYS = {4: "spectral_projection", 5: "gate_logits", 6: "kv_mask_kernel", 7: "reconstruction"}
@@ -79,6 +84,99 @@ def cpu_baseline(cfg, inp, sample: int):
             g["k"], xbar)
 
 
+def backward_main(args, cfg, inp, L, desc, params, ws, xt, k) -> int:
+    """Training pair: the gate's forward (x~, k) and its backward (dx, dU, dW, db)."""
+    import torch
+    import workloads.dynakv as kv
+    x, U, W, b = params
+    n, d = cfg.n, cfg.d
+    tdt = xt.dtype
+    g_np, _ = kv.upstream(cfg)
+    g_xhat = to_device(g_np)
+    g_const = 2 * 0.5 * 0.44 / (n * d)
+    ws_b = torch.empty(L.dynakv_bwd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    dx = torch.empty(n, d, dtype=tdt, device="cuda")
+    dU = torch.empty(d, d, dtype=torch.float32, device="cuda")
+    dW = torch.empty(d, d, dtype=torch.float32, device="cuda")
+    db = torch.empty(d, dtype=torch.float32, device="cuda")
+
+    def step():
+        L.dynakv_gate(desc, x, U, W, b, cfg.tau, xt, k, None, None, ws)
+        L.dynakv_gate_bwd(desc, x, U, W, b, xt, g_xhat, None, g_const, dx, dU, dW, db, ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if L.dynakv_check(ws_b) != 0:
+        print("bench_dynakv.py: device-side range error", file=sys.stderr)
+        return 4
+    L.lmhead_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = {kind: L.lmhead_timing_read(kind) for kind in BWD_KINDS}
+    L.lmhead_timing_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    log(f"{ms_per_step:.3f} ms/step (gate forward + backward)")
+    esz = 2 if cfg.dtype == "bf16" else 4
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
+    dense = 2.0 * n * d * d
+    # algorithmic bytes per launch: mask backward reads logits (4), x~ and g_xhat (esz each) and writes
+    # g_l and g_xhat*m (esz each); a transpose pair reads and writes two [n x d] operands
+    byts = {6: n * d * 4.0, 8: n * d * (4.0 + 4 * esz), 13: 4.0 * n * d * esz}
+    kinds = []
+    for kind, name in BWD_KINDS.items():
+        ms, cnt = kern[kind]
+        avg = ms / cnt if cnt else 0.0
+        if kind in byts:
+            rate = byts[kind] / (avg * 1e-3) / 1e9 if avg else 0.0
+            kinds.append({"kernel": name, "kind": kind, "launches": int(cnt), "avg_ms": avg, "bound": "hbm",
+                          "gbs": rate, "frac": rate / PEAK_HBM_GBS})
+        else:
+            rate = dense / (avg * 1e-3) / 1e12 if avg else 0.0
+            kinds.append({"kernel": name, "kind": kind, "launches": int(cnt), "avg_ms": avg, "bound": "mfma",
+                          "tflops": rate, "frac": rate / peak})
+    per_step = {e["kernel"]: e["avg_ms"] * e["launches"] / args.steps for e in kinds}
+    dom = max(kinds, key=lambda e: e["avg_ms"] * e["launches"])
+    if dom["bound"] == "mfma":
+        roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak,
+                    "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "avg_launch_ms": dom["avg_ms"]}
+    else:
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": dom["frac"], "traffic": None, "avg_launch_ms": dom["avg_ms"]}
+    cpu = None
+    if args.cpu_rows > 0:
+        import workloads as wl
+        from oracle import dynakv_oracle as O
+        m = min(args.cpu_rows, n)
+        log(f"timing the oracle's forward + backward on {m} tokens")
+        f = wl.as_f64
+        xs, gs = f(inp["x"][:m]), f(g_np[:m])
+        t0 = time.perf_counter()
+        O.gate(xs, f(inp["U"]), f(inp["W"]), inp["b"], cfg.tau, store_dtype=cfg.dtype)
+        o = O.gate_bwd(xs, f(inp["U"]), f(inp["W"]), inp["b"], gs, np.full((m, d), g_const), store_dtype=cfg.dtype)
+        dt = time.perf_counter() - t0
+        got = dx[:m].double().cpu().numpy()
+        cpu = {"value": m / dt, "unit": "tokens/s", "cores": os.cpu_count() or 1, "kind": "oracle",
+               "sample": f"the first {m} tokens of the same workload: fp64 gate forward and backward ({dt:.1f} s)",
+               "gpu_vs_oracle_rel_fro_dx_on_sample": float(np.linalg.norm(got - o["dx"]) / np.linalg.norm(o["dx"]))}
+    out = {
+        "metric": "tokens/s KV gate forward + backward (training, 1 GPU)",
+        "value": n / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"kv_configs[{args.config}] {cfg.name} (gate forward + backward)", "n": n, "d_kv": d},
+        "step_tflops": 7 * dense / (ms_per_step * 1e-3) / 1e12,
+        "roofline": roofline, "kernels": kinds, "ms_per_step_by_kernel": per_step, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +185,8 @@ def main(argv=None) -> int:
     ap.add_argument("--config", type=int, default=2, help="index into workloads.dynakv.KV_CONFIGS")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="tokens of the oracle sample (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the training pair dynakv_gate + dynakv_gate_bwd instead of gate + store + reconstruction")
     args = ap.parse_args(argv)
     if args.gpus != 1:
         print("bench_dynakv.py: this build runs on ONE GPU only; use --gpus 1", file=sys.stderr)
@@ -116,6 +216,9 @@ def main(argv=None) -> int:
     off = torch.empty(n + 1, dtype=torch.int64, device="cuda")
     packed = torch.empty(n * d, dtype=tdt, device="cuda")
     xbar = torch.empty(n, d, dtype=tdt, device="cuda")
+
+    if args.backward:
+        return backward_main(args, cfg, inp, L, desc, (x, U, W, b), ws, xt, k)
 
     def step():
         L.dynakv_gate(desc, x, U, W, b, cfg.tau, xt, k, None, None, ws)

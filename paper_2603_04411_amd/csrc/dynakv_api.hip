@@ -263,8 +263,8 @@ int dynakv_gate_bwd(const dynakv_desc* desc, const void* x, const void* U, const
   auto param_grad = [&](const void* rows_src, int64_t ld_rows, const void* cols_src, int kind, float* out) -> int {
     {
       TimedLaunch tl(13, s);
-      LM_TRY(launch_transpose(dt, rows_src, ld_rows, L.n, d, false, hdr, at(L.T1), L.ldK, L.ncap, L.dp, s));
-      LM_TRY(launch_transpose(dt, cols_src, d, L.n, d, false, hdr, at(L.T2), L.ldK, L.ncap, L.dp, s));
+      LM_TRY(launch_kv_transpose(dt, rows_src, ld_rows, L.n, d, at(L.T1), L.ldK, L.ncap, (int)L.dp, s));
+      LM_TRY(launch_kv_transpose(dt, cols_src, d, L.n, d, at(L.T2), L.ldK, L.ncap, (int)L.dp, s));
     }
     GemmTArgs ta{};
     ta.A = at(L.T2);

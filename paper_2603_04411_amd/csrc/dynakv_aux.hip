@@ -200,7 +200,8 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
 // order); the workgroup's four strips are summed at the end into one row of dbpart.
 // NG as in kv_mask_kernel: NG > 0 keeps the row, r and g_xhat in registers; NG == 0 re-reads.
 template <typename T, int NG>
-__global__ __launch_bounds__(256) void kv_mask_bwd_kernel(const float* __restrict__ logits,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NG > 0 && NG <= 4 ? 4 : 2)))
+void kv_mask_bwd_kernel(const float* __restrict__ logits,
                                                           const float* __restrict__ bias,
                                                           const T* __restrict__ xt, const T* __restrict__ gxh,
                                                           const float* __restrict__ gm, float gmc, int64_t n,
@@ -426,14 +427,29 @@ __global__ __launch_bounds__(256) void kv_mask_bwd_kernel(const float* __restric
   }
 }
 
-// out[j] (+)= sum over the rows of part, in row order.
+// out[j] (+)= sum over the rows of part.  A workgroup owns 64 columns; its four wavefronts each sum
+// every fourth row (four independent running sums each), and the partial sums are combined in a fixed
+// order, so the result does not depend on the launch.
 __global__ __launch_bounds__(256) void kv_sum_rows_kernel(const float* __restrict__ part, int rows, int64_t row_pitch,
                                                           int64_t len, float* __restrict__ out, int accumulate) {
-  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (j >= len) return;
-  float t = part[j];
-  for (int r = 1; r < rows; ++r) t += part[r * row_pitch + j];
-  out[j] = accumulate ? out[j] + t : t;
+  __shared__ float sm[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int64_t j = (int64_t)blockIdx.x * 64 + cl;
+  float t[4] = {0.f, 0.f, 0.f, 0.f};
+  if (j < len) {
+    int r = rl;
+    for (; r + 12 < rows; r += 16) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) t[u] += part[(int64_t)(r + 4 * u) * row_pitch + j];
+    }
+    for (; r < rows; r += 4) t[0] += part[(int64_t)r * row_pitch + j];
+  }
+  sm[rl][cl] = (t[0] + t[1]) + (t[2] + t[3]);
+  __syncthreads();
+  if (rl == 0 && j < len) {
+    const float v = (sm[0][cl] + sm[1][cl]) + (sm[2][cl] + sm[3][cl]);
+    out[j] = accumulate ? out[j] + v : v;
+  }
 }
 
 // Row-padded copy of a parameter matrix: 16 bytes per thread, zero beyond the source's extent.
@@ -448,6 +464,49 @@ __global__ __launch_bounds__(256) void kv_pad_copy_kernel(const char* __restrict
   uint4 v = make_uint4(0u, 0u, 0u, 0u);
   if (r < rows && c < row_bytes) v = *reinterpret_cast<const uint4*>(in + r * in_pitch + c);
   *reinterpret_cast<uint4*>(out + r * out_pitch + c) = v;
+}
+
+// out[c][r] = in[r][c] for r < rows, c < cols, zero up to [cols_p x rows_p]: 64 x 64 tiles with 16-byte
+// global accesses on both sides.  Rows of the source go to LDS as they are (padded pitch); each thread
+// then gathers the 16 bytes of one output chunk (consecutive r of one column) from LDS.
+// Requires 16-byte aligned rows on both sides and cols, cols_p, rows_p multiples of 64.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_transpose_kernel(const T* __restrict__ in, int64_t ld_in, int64_t rows,
+                                                           int cols, T* __restrict__ out, int64_t ld_out) {
+  constexpr int VEC = 16 / sizeof(T);         // elements per 16-byte chunk
+  constexpr int CPR = 64 / VEC;               // chunks per tile row
+  constexpr int PITCH = 64 + 4 / sizeof(T);   // elements; keeps rows 4-byte aligned and the gather conflict-free
+  __shared__ __attribute__((aligned(16))) T tile[64 * PITCH];
+  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+#pragma unroll
+  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
+    const int id = pass * 256 + threadIdx.x;
+    const int rr = id / CPR, cc = id % CPR;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r0 + rr < rows && c0 < cols) v = *reinterpret_cast<const uint4*>(in + (r0 + rr) * ld_in + c0 + cc * VEC);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(tile + rr * PITCH + cc * VEC);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
+    const int id = pass * 256 + threadIdx.x;
+    const int c = id / CPR, rc = id % CPR;
+    T e[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) e[i] = tile[(rc * VEC + i) * PITCH + c];
+    uint4 v;
+    if constexpr (sizeof(T) == 2) {
+      v.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
+      v.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
+      v.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
+      v.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
+    } else {
+      v = make_uint4(e[0], e[1], e[2], e[3]);
+    }
+    *reinterpret_cast<uint4*>(out + (int64_t)(c0 + c) * ld_out + r0 + rc * VEC) = v;
+  }
 }
 
 // ---- ragged store ---------------------------------------------------------------------------
@@ -797,7 +856,7 @@ hipError_t launch_kv_mask_bwd(int dtype, const float* logits, const float* b, co
 
 hipError_t launch_kv_sum_rows(const float* part, int rows, int64_t row_pitch, int64_t len, float* out,
                               bool accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(kv_sum_rows_kernel, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, s, part, rows, row_pitch,
+  hipLaunchKernelGGL(kv_sum_rows_kernel, dim3((unsigned)((len + 63) / 64)), dim3(256), 0, s, part, rows, row_pitch,
                      len, out, accumulate ? 1 : 0);
   return hipGetLastError();
 }
@@ -809,6 +868,18 @@ hipError_t launch_kv_pad_copy(int dtype, const void* in, int64_t ld_in, int rows
   hipLaunchKernelGGL(kv_pad_copy_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
                      static_cast<const char*>(in), ld_in * esz, rows, cols * esz, static_cast<char*>(out),
                      ld_out * esz, rows_p);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows, int cols, void* out,
+                               int64_t ld_out, int64_t rows_p, int cols_p, hipStream_t s) {
+  const dim3 grid((unsigned)(rows_p / 64), (unsigned)(cols_p / 64));
+  if (dtype == LMHEAD_BF16)
+    hipLaunchKernelGGL(kv_transpose_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), ld_in,
+                       rows, cols, static_cast<uint16_t*>(out), ld_out);
+  else
+    hipLaunchKernelGGL(kv_transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t*>(in), ld_in,
+                       rows, cols, static_cast<uint32_t*>(out), ld_out);
   return hipGetLastError();
 }
 

@@ -65,7 +65,9 @@ struct KvBwdLayout {
   size_t hdr, Wp, Up, WT, logits, gl, gxt, T1, T2, part, dbpart, total;
 };
 
-constexpr int kKvBwdMaxBlocks = 2048;
+// Workgroups of the mask backward kernel: four 256-thread workgroups fit a compute unit (128 VGPRs),
+// so 1024 is one resident round on 256 compute units; each wavefront loops over its share of tokens.
+constexpr int kKvBwdMaxBlocks = 1024;
 
 static inline KvBwdLayout make_kv_bwd_layout(const dynakv_desc* d) {
   KvBwdLayout L{};
@@ -171,13 +173,18 @@ hipError_t launch_kv_mask_bwd(int dtype, const float* logits, const float* b, co
                               const float* g_m, float g_m_const, int64_t n, int d, bool literal, void* gl,
                               void* a_out, float* dbpart, int nblk, hipStream_t s);
 
-// out[j] (+)= sum_r part[r][j] for j < len, rows (pitch row_pitch floats) summed in order.
+// out[j] (+)= sum_r part[r][j] for j < len (rows of pitch row_pitch floats), in a fixed order.
 hipError_t launch_kv_sum_rows(const float* part, int rows, int64_t row_pitch, int64_t len, float* out,
                               bool accumulate, hipStream_t s);
 
 // out[r][c] = in[r][c] for r < rows, c < cols; zero up to [rows_p x ld_out].
 hipError_t launch_kv_pad_copy(int dtype, const void* in, int64_t ld_in, int rows, int cols, void* out,
                               int64_t ld_out, int rows_p, hipStream_t s);
+
+// out[c][r] = in[r][c] for r < rows, c < cols; zero up to [cols_p x rows_p] (pitch ld_out).  Rows of both
+// sides 16-byte aligned; cols, cols_p, rows_p multiples of 64.
+hipError_t launch_kv_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows, int cols, void* out,
+                               int64_t ld_out, int64_t rows_p, int cols_p, hipStream_t s);
 
 hipError_t launch_kv_clear_header(WsHeader* hdr, hipStream_t s);
 

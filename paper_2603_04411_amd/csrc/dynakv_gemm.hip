@@ -16,6 +16,8 @@
 #include "dynakv_common.h"
 #include "gemm_core.h"
 
+#include <type_traits>
+
 namespace lmhead {
 
 namespace {
@@ -132,8 +134,25 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   const int h = G::lane() / CH;                   // which of the instruction's rows this lane works on
   const int c = G::lane() % CH;                   // its 16-byte chunk of the row = 4 output columns
   const int m = m0 + c * 4;
+  constexpr int IPW = RPW / RPI;                  // instructions per wave and phase
+  using OldT = typename std::conditional<ESZ == 2, bf16x4_t, f32x4_t>::type;
+  const bool accumulate = Mode != 2 && a.accumulate && m < a.M;
 #pragma unroll
   for (int jg = 0; jg < NPH; ++jg) {
+    // When the tile is added to what the output holds, the old values of all the rows this wave writes
+    // in this phase are requested now, so that their latency runs under the staging of the tile and is
+    // paid once per phase.  (Dense modes only: the output row of a staged row is n0 + its tile column.)
+    OldT oldv[IPW];
+    if constexpr (Mode != 2) {
+      if (accumulate) {
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+          const int64_t row = n0 + tile_col(jg, (G::wave() + G::NWAVES * i) * RPI + h);
+          oldv[i] = OldT{};
+          if (row < a.Nn) oldv[i] = *reinterpret_cast<const OldT*>(static_cast<const char*>(a.out_e) + (row * a.ldo + m) * ESZ);
+        }
+      }
+    }
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj) {
       const int j = jg * JG + jj;
@@ -157,7 +176,6 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
       const int r = (G::wave() + G::NWAVES * (idx / RPI)) * RPI + idx % RPI;
       my_row = ph < NPH ? rows_lds[tile_col(ph, r)] : -1;
     }
-    constexpr int IPW = RPW / RPI;                // instructions per wave and phase
     constexpr int RB = IPW < 8 ? IPW : 8;
 #pragma unroll
     for (int i0 = 0; i0 < IPW; i0 += RB) {
@@ -176,24 +194,12 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
         orow[u] = m < a.M ? row : -1;
       }
       if constexpr (Mode != 2) {
-        // the batch's old values are all requested before the first of them is used
-        if (a.accumulate) {
-          f32x4_t old[RB];
+        if (accumulate) {
 #pragma unroll
           for (int u = 0; u < RB; ++u) {
-            old[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            if (orow[u] < 0) continue;
-            if (a.out_f) {
-              old[u] = *reinterpret_cast<const f32x4_t*>(a.out_f + orow[u] * a.ldo + m);
-            } else if constexpr (ESZ == 4) {
-              old[u] = *reinterpret_cast<const f32x4_t*>(static_cast<const float*>(a.out_e) + orow[u] * a.ldo + m);
-            } else {
-              const bf16x4_t hb = *reinterpret_cast<const bf16x4_t*>(static_cast<const __bf16*>(a.out_e) + orow[u] * a.ldo + m);
-              old[u] = f32x4_t{(float)hb.x, (float)hb.y, (float)hb.z, (float)hb.w};
-            }
+            const OldT o = oldv[i0 + u];
+            v[u] += f32x4_t{(float)o.x, (float)o.y, (float)o.z, (float)o.w};
           }
-#pragma unroll
-          for (int u = 0; u < RB; ++u) v[u] += old[u];
         }
       }
 #pragma unroll
@@ -228,6 +234,7 @@ hipError_t launch_mode(const KvGemmArgs& a, hipStream_t s) {
   using G = KvTile<E, Mode == 2>;
   const int mtiles = (a.M + G::BM - 1) / G::BM;
   const int64_t ntiles = (a.Nn + G::BN - 1) / G::BN;
+  if (a.accumulate && (Mode == 2 || a.out_f || !a.out_e)) return hipErrorInvalidValue;
   KvGemmArgs b = a;
   b.walk_len = (int)xcd_grid_size(mtiles, ntiles, kKvMapBy);
   const unsigned resident = (unsigned)compute_units() / kNumXcd * kNumXcd * kKvWgPerCu;   // LDS-bound
