@@ -217,6 +217,13 @@ def main(argv=None) -> int:
     packed = torch.empty(n * d, dtype=tdt, device="cuda")
     xbar = torch.empty(n, d, dtype=tdt, device="cuda")
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.backward:
         return backward_main(args, cfg, inp, L, desc, (x, U, W, b), ws, xt, k)
 
@@ -225,13 +232,6 @@ def main(argv=None) -> int:
         L.dynakv_store(desc, xt, k, 0, off, packed, n * d, ws)
         L.dynakv_reconstruct(desc, packed, n * d, off, k, Ui, xbar, ws)
 
-    if args.calibrate_copy:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
