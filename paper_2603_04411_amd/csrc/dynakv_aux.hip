@@ -198,7 +198,7 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
 // One wavefront per token, looping over tokens with the grid's stride.  Each wavefront adds its g_l
 // rows into its own strip of LDS (a lane always owns the same positions, so no atomics and a fixed
 // order); the workgroup's four strips are summed at the end into one row of dbpart.
-// NG as in kv_mask_kernel: NG > 0 keeps the row, r and g_xhat in registers; NG == 0 re-reads.
+// NG as in kv_mask_kernel: NG > 0 keeps the row and q (then r) in registers; NG == 0 re-reads.
 template <typename T, int NG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NG > 0 && NG <= 4 ? 4 : 2)))
 void kv_mask_bwd_kernel(const float* __restrict__ logits,
@@ -295,22 +295,25 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
         }
       }
     };
-    // q of group g turned into r: the inclusive prefix sums over all positions up to each one
-    auto prefix = [&](int g, float& carry, float (&r)[4], float (&gx)[4]) {
+    // q of group g (0 beyond d) and the g_xhat values it was formed from
+    auto load_q = [&](int g, float (&q)[4], float (&gx)[4]) {
       const int i0 = g * 256 + lane * 4;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) r[e] = gx[e] = 0.f;
+      for (int e = 0; e < 4; ++e) q[e] = gx[e] = 0.f;
       if (i0 < d) {
         float xv[4];
         Store4<T>::load(xt + tok * d + i0, xv);
         Store4<T>::load(gxh + tok * d + i0, gx);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r[e] = gx[e] * xv[e] + gmc;
+        for (int e = 0; e < 4; ++e) q[e] = gx[e] * xv[e] + gmc;
         if (gm) {
           const float4 t = *reinterpret_cast<const float4*>(gm + tok * d + i0);
-          r[0] += t.x; r[1] += t.y; r[2] += t.z; r[3] += t.w;
+          q[0] += t.x; q[1] += t.y; q[2] += t.z; q[3] += t.w;
         }
       }
+    };
+    // q of one group turned, in place, into r: the inclusive prefix sums over all positions up to each one
+    auto scan_prefix = [&](float& carry, float (&r)[4]) {
       r[1] += r[0];
       r[2] += r[1];
       r[3] += r[2];
@@ -326,31 +329,11 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
       for (int e = 0; e < 4; ++e) r[e] += below;
     };
 
-    // r and s = sum_i p_i r_i
-    float rk[NR][4], gxk[NR][4];
-    float s = 0.f;
+    // m (suffix sums, last group first), a = g_xhat * m, and q (kept when the row is held in registers)
+    float qk[NR][4];
     {
       float carry = 0.f;
-      auto step = [&](int g, float (&r)[4], float (&gx)[4]) {
-        prefix(g, carry, r, gx);
-        float ex[4];
-        expo(g, ex);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) s += ex[e] * r[e];
-      };
-      if constexpr (NG > 0) {
-#pragma unroll
-        for (int g = 0; g < NG; ++g) step(g, rk[g], gxk[g]);
-      } else {
-        for (int g = 0; g < ngroups; ++g) step(g, rk[0], gxk[0]);
-      }
-    }
-    s = wave_sum(s) * inv;
-
-    // m (suffix sums, last group first) and a = g_xhat * m
-    {
-      float carry = 0.f;
-      auto step = [&](int g, const float (&gx_kept)[4]) {
+      auto step = [&](int g, float (&q)[4]) {
         const int i0 = g * 256 + lane * 4;
         float sfx[4];
         expo(g, sfx);
@@ -365,14 +348,9 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
         }
         const float above = carry + (incl - sfx[0]);
         carry += __shfl(incl, 0);
+        float gx[4];
+        load_q(g, q, gx);
         if (i0 < d) {
-          float gx[4];
-          if constexpr (NG > 0) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) gx[e] = gx_kept[e];
-          } else {
-            Store4<T>::load(gxh + tok * d + i0, gx);
-          }
 #pragma unroll
           for (int e = 0; e < 4; ++e) gx[e] *= (above + sfx[e]) * inv;
           Store4<T>::store(a_out + tok * d + i0, gx);
@@ -380,11 +358,35 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
       };
       if constexpr (NG > 0) {
 #pragma unroll
-        for (int g = NG - 1; g >= 0; --g) step(g, gxk[g]);
+        for (int g = NG - 1; g >= 0; --g) step(g, qk[g]);
       } else {
-        for (int g = ngroups - 1; g >= 0; --g) step(g, gxk[0]);
+        for (int g = ngroups - 1; g >= 0; --g) step(g, qk[0]);
       }
     }
+
+    // r (in place of q) and s = sum_i p_i r_i
+    float s = 0.f;
+    {
+      float carry = 0.f;
+      auto step = [&](int g, float (&r)[4]) {
+        if constexpr (NG == 0) {
+          float gx[4];
+          load_q(g, r, gx);
+        }
+        scan_prefix(carry, r);
+        float ex[4];
+        expo(g, ex);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += ex[e] * r[e];
+      };
+      if constexpr (NG > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) step(g, qk[g]);
+      } else {
+        for (int g = 0; g < ngroups; ++g) step(g, qk[0]);
+      }
+    }
+    s = wave_sum(s) * inv;
 
     // g_l = p (r - s), stored in gate column order and added to the wavefront's column sums
     {
@@ -393,7 +395,8 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
         const int i0 = g * 256 + lane * 4;
         if constexpr (NG == 0) {
           float gx[4];
-          prefix(g, carry, r, gx);
+          load_q(g, r, gx);
+          scan_prefix(carry, r);
         }
         float ex[4];
         expo(g, ex);
@@ -414,9 +417,9 @@ void kv_mask_bwd_kernel(const float* __restrict__ logits,
       };
       if constexpr (NG > 0) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) step(g, rk[g]);
+        for (int g = 0; g < NG; ++g) step(g, qk[g]);
       } else {
-        for (int g = 0; g < ngroups; ++g) step(g, rk[0]);
+        for (int g = 0; g < ngroups; ++g) step(g, qk[0]);
       }
     }
   }
