@@ -12,11 +12,13 @@
 // from global memory straight into LDS (buffer_load_dwordx4 ... lds, no register staging).
 // LDS is a ring of five 32 KB slots, each holding one operand's tile for one K-step; the
 // units A(0) B(0) A(1) B(1) ... (or B first) go round the ring, so besides the two units being
-// multiplied, three are resident or in flight.  During K-step k a wave issues the loads of
-// B(k+1) (first half of the step) and A(k+2) (second half) into the two slots that the
-// barrier ending K-step k-1 has freed, one load behind every fourth MFMA: the vector L1
-// then never sees a burst (a burst backs up the address queue and blocks the wave's
-// in-order issue, MFMAs included), and every load still has half a K-step or more to land.
+// multiplied, three are resident or in flight.  The barrier near the end of K-step k frees the
+// slots of A(k) and B(k); a wave issues the loads of B(k+2) into the first of them straight away
+// (last quarter of step k and first quarter of step k+1) and those of A(k+3) into the second
+// during the middle half of step k+1, so no slot is ever idle: B has half a K-step to a whole
+// one to land before the barrier that hands it over, A one to one and a half.  Loads go one
+// behind every fourth MFMA: the vector L1 then never sees a burst (a burst backs up the address
+// queue and blocks the wave's in-order issue, MFMAs included).
 // One workgroup barrier per K-step; a unit is complete when each wave's own vmcnt has
 // drained past it (loads retire in order) and all waves have passed that barrier.
 //
@@ -325,52 +327,56 @@ struct GemmTile {
       int sA = 0, sB = 1;
       issue_x(0, 0, 0); issue_x(0, 0, 1);
       issue_y(0, 1, 0); issue_y(0, 1, 1);
-      if (ksteps > 1) { issue_x(1, 2, 0); issue_x(1, 2, 1); }
-      if (ksteps > 1)
-        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
-      else
+      if (ksteps > 1) {
+        issue_x(1, 2, 0); issue_x(1, 2, 1);
+        issue_y(1, 3, 0);
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD + A_LD / NPART));
+      } else {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      }
       __builtin_amdgcn_s_barrier();
       frags_xy(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
-      // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) are resident or in flight; the
-      // slots of X(ks-1) and Y(ks-1) are free (all waves passed the barrier after reading them).
+      // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) and the first half of Y(ks+1) are
+      // resident or in flight; the slot of Y(ks-1) is free.  The barrier near the end of the step
+      // frees the slots of X(ks) and Y(ks), and the first of them is put to use at once (Y(ks+2)),
+      // so no slot is ever idle: Y has half a K-step to a whole one to land, X one to one and a half.
       for (; ks + 2 < ksteps; ++ks) {
         const char* ca = lds + sA * SLOT;
         const char* cb = lds + sB * SLOT;
         const int sB1 = next_slot(sB, 2);   // slot of Y(ks+1) == slot of X(ks-1)
         const int sA1 = next_slot(sA, 2);   // slot of X(ks+1)
         const int sA2 = next_slot(sA1, 2);  // slot of X(ks+2) == slot of Y(ks-1)
-        // sub-step 0 and 1: first and second half of Y(ks+1)
+        // sub-step 0: second half of Y(ks+1)
         frags_xy(ca, cb, 1, 1);
-        issue_y(ks + 1, sB1, 0);
+        issue_y(ks + 1, sB1, 1);
         mma_all(0);
         sched_region(LD_REGION_B);
+        // sub-steps 1 and 2: X(ks+2)
         frags_xy(ca, cb, 2, 0);
-        issue_y(ks + 1, sB1, 1);
-        mma_all(1);
-        sched_region(LD_REGION_B);
-        // sub-step 2: first half of X(ks+2)
-        frags_xy(ca, cb, 3, 1);
         issue_x(ks + 2, sA2, 0);
+        mma_all(1);
+        sched_region(LD_REGION);
+        frags_xy(ca, cb, 3, 1);
+        issue_x(ks + 2, sA2, 1);
         mma_all(0);
         sched_region(LD_REGION);
-        // hand-over: everything but the youngest A_LD/2 loads of this wave has landed
-        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD / NPART));
+        // hand-over: everything but X(ks+2), this wave's youngest A_LD loads, has landed
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the rest of X(ks+2);
-        // its target slot was freed by the barrier that ended K-step ks-1, not by this one
+        // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the first half of Y(ks+2),
+        // which goes into the slot of X(ks) that this barrier has just freed
         frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
-        issue_x(ks + 2, sA2, 1);
+        issue_y(ks + 2, sA, 0);
         mma_all(1);
-        sched_region(LD_REGION);
+        sched_region(LD_REGION_B);
         sA = sA1;
         sB = sB1;
       }
-      // drain: the last two K-steps
+      // drain: the last two K-steps (the first half of Y(ks+1) is already under way)
       for (; ks < ksteps; ++ks) {
         const char* ca = lds + sA * SLOT;
         const char* cb = lds + sB * SLOT;
@@ -378,11 +384,10 @@ struct GemmTile {
         const int sA1 = next_slot(sA, 2);
         const bool more = ks + 1 < ksteps;
         frags_xy(ca, cb, 1, 1);
-        if (more) issue_y(ks + 1, sB1, 0);
+        if (more) issue_y(ks + 1, sB1, 1);
         mma_all(0);
         __builtin_amdgcn_sched_barrier(0);
         frags_xy(ca, cb, 2, 0);
-        if (more) issue_y(ks + 1, sB1, 1);
         mma_all(1);
         __builtin_amdgcn_sched_barrier(0);
         frags_xy(ca, cb, 3, 1);
