@@ -199,14 +199,12 @@ __global__ __launch_bounds__(256) void kv_mask_kernel(const float* __restrict__ 
 // rows into its own strip of LDS (a lane always owns the same positions, so no atomics and a fixed
 // order); the workgroup's four strips are summed at the end into one row of dbpart.
 // NG as in kv_mask_kernel: NG > 0 keeps the row and q (then r) in registers; NG == 0 re-reads.
+// Up to d = 1024 the kernel is held to 128 VGPRs so that four workgroups share a compute unit.
 template <typename T, int NG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NG > 0 && NG <= 4 ? 4 : 2)))
-void kv_mask_bwd_kernel(const float* __restrict__ logits,
-                                                          const float* __restrict__ bias,
-                                                          const T* __restrict__ xt, const T* __restrict__ gxh,
-                                                          const float* __restrict__ gm, float gmc, int64_t n,
-                                                          int d, int literal, T* __restrict__ gl,
-                                                          T* __restrict__ a_out, float* __restrict__ dbpart) {
+void kv_mask_bwd_kernel(const float* __restrict__ logits, const float* __restrict__ bias, const T* __restrict__ xt,
+                        const T* __restrict__ gxh, const float* __restrict__ gm, float gmc, int64_t n, int d,
+                        int literal, T* __restrict__ gl, T* __restrict__ a_out, float* __restrict__ dbpart) {
   extern __shared__ float colsum[];   // [4][d], position order
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
