@@ -118,9 +118,9 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   // The tile leaves through LDS as [n][m] rows of fp32 (as many tile columns per phase as fit) so that
   // each output row segment is written with 16 bytes per lane for fp32 and 8 for bf16, a whole
   // number of rows per wavefront instruction.
-  constexpr int JG = G::LDS_BYTES >= G::BN * (G::BM * 4 + 16) + G::BN * 4 ? G::TN : G::TN / 2;
+  constexpr int JG = G::LDS_BYTES >= G::BN * (G::BM * 4 + 16) + G::BN * 4 ? G::TN : G::TN / 2;   // blocks per wave and phase
   constexpr int NPH = G::TN / JG;                 // phases
-  constexpr int NCOL = G::WGN * JG * 32;          // tile columns staged per phase
+  constexpr int NCOL = G::WGN * JG * G::NB;       // tile columns staged per phase
   constexpr int P = G::BM * 4 + 16;               // staging row pitch in bytes
   constexpr int CH = G::BM * 4 / 16;              // lanes per staged row
   constexpr int RPI = 64 / CH;                    // staged rows per wavefront instruction
@@ -130,7 +130,9 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
   int* rows_lds = reinterpret_cast<int*>(smem + NCOL * P);
   if (threadIdx.x < G::BN) rows_lds[threadIdx.x] = my_row;
   // staged row -> tile column
-  auto tile_col = [&](int phase, int r) { return (r / (JG * 32)) * G::WN + phase * (JG * 32) + r % (JG * 32); };
+  auto tile_col = [&](int phase, int r) {
+    return (r / (JG * G::NB)) * G::WN + phase * (JG * G::NB) + r % (JG * G::NB);
+  };
   const int h = G::lane() / CH;                   // which of the instruction's rows this lane works on
   const int c = G::lane() % CH;                   // its 16-byte chunk of the row = 4 output columns
   const int m = m0 + c * 4;
@@ -156,11 +158,11 @@ __device__ inline void kv_tile(const KvGemmArgs& a, int wg, char* smem) {
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj) {
       const int j = jg * JG + jj;
-      const int nl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);
+      const int nl = G::wave_n() * (JG * G::NB) + jj * G::NB + (G::lane() % G::NB);
 #pragma unroll
       for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < G::VB / 4; ++q) {
           const f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
           *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
         }

@@ -27,20 +27,21 @@
 // bytes at wave_base + 16 L, i.e. row L/8, position L%8 of an 8-row group, so lane L
 // simply fetches the global chunk (L%8) ^ swz(row).
 //
-// Fragment layout used for both operands (what matters is only that A and B agree):
-// lane l of a 32-row block holds row l % 32 and the 16-byte chunk 2*s + l/32 of K
-// sub-step s (four sub-steps per K-step).  For bf16 one v_mfma_f32_32x32x16_bf16 consumes
-// the chunk; for fp32 the chunk's four floats feed four v_mfma_f32_32x32x2_f32.
-// Fragments are double-buffered in registers and the pipeline is skewed so that the
-// barrier falls before the last sub-step: its MFMAs overlap the first fragment reads of
-// the next stage and the issue of the next loads.
+// Fragment layout used for both operands (what matters is only that A and B agree): the wave tile
+// is cut into NB x NB MFMA blocks; lane l of a block holds row l % NB and, in K sub-step s, the
+// 16-byte chunk (64 / NB) * s + l / NB of the row's 128-byte K slice.
+//   bf16: NB = 16, v_mfma_f32_16x16x32_bf16, two sub-steps per K-step.  Per flop this form moves half
+//         the accumulator data of the 32x32x16 form, and the part is power-limited: on static random
+//         operands a bare loop of it sustains 2092 TFLOP/s against 1843 for 32x32x16 (2447 / 2482 on
+//         zeros).  -DLMHEAD_BF16_BLOCK=32 builds the 32x32x16 form (four sub-steps) for comparison.
+//   fp32: NB = 32, the chunk's four floats feed four v_mfma_f32_32x32x2_f32, four sub-steps.
+//   e4m3: NB = 32, v_mfma_f32_32x32x64_f8f6f4, two chunks per lane and sub-step, two sub-steps.
+// Fragments are double-buffered in registers and the hand-over barrier is skewed so that the MFMAs
+// after it overlap the first fragment reads of the next K-step and the issue of the next loads.
 //
-// 8-bit (e4m3) operands use v_mfma_f32_32x32x64_f8f6f4: a K-step is then 128 values of K, consumed
-// in two sub-steps of two chunks per lane; run_rows() has a second loop body for that case with the
-// same ring and the same four-region rhythm.
-//
-// Accumulator layout of a 32x32 block (16 floats per lane):
-//   element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4,  n = l % 32.
+// Accumulator layout of a block (NB * NB / 64 floats per lane); a lane owns one column n = l % NB:
+//   NB = 32: element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4   (16 values)
+//   NB = 16: element v of lane l  <->  m = 4*(l/16) + v               (4 values)
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -65,23 +66,39 @@ struct fp8_tag {};   // OCP e4m3 operands (logits only), fp32 accumulation
 
 template <typename E>
 struct Elem;
+#ifndef LMHEAD_BF16_BLOCK
+#define LMHEAD_BF16_BLOCK 16
+#endif
 template <>
 struct Elem<bf16_tag> {
   static constexpr int size = 2;
   static constexpr int dtype = 1;
+  static constexpr int block = LMHEAD_BF16_BLOCK;   // MFMA block edge: 16 (16x16x32) or 32 (32x32x16)
   static constexpr int frag_chunks = 1;   // 16-byte chunks of K per lane and MFMA group
   static constexpr int mfma_per_block = 1;
+  using acc_t = std::conditional<block == 16, f32x4_t, f32x16_t>::type;
   __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[1], const u32x4_t (&b)[1]) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[0]),
                                                 __builtin_bit_cast(bf16x8_t, b[0]), c, 0, 0, 0);
+  }
+  // Written as an asm statement with the accumulator tied to one AGPR tuple: with the builtin the
+  // register allocator does not keep sixty-four 4-register accumulators in place across the loop
+  // (hundreds of v_accvgpr moves per K-step, and spills).  The compiler then neither knows the
+  // instruction's latency nor counts it as an MFMA for scheduling hints: the main loop for this
+  // form spells out its interleave in program order, and run_rows() ends with the wait states
+  // that reading a just-written accumulator needs.
+  __device__ static inline void mma(f32x4_t& c, const u32x4_t (&a)[1], const u32x4_t (&b)[1]) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a[0]), "v"(b[0]));
   }
 };
 template <>
 struct Elem<f32_tag> {
   static constexpr int size = 4;
   static constexpr int dtype = 0;
+  static constexpr int block = 32;
   static constexpr int frag_chunks = 1;
   static constexpr int mfma_per_block = 4;
+  using acc_t = f32x16_t;
   __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[1], const u32x4_t (&b)[1]) {
     // whole-vector casts, then named components: element-wise bit casts of a[q] are avoided
     const f32x4_t fa = __builtin_bit_cast(f32x4_t, a[0]);
@@ -96,8 +113,10 @@ struct Elem<f32_tag> {
 template <>
 struct Elem<fp8_tag> {
   static constexpr int size = 1;
+  static constexpr int block = 32;
   static constexpr int frag_chunks = 2;   // 32 bytes = 32 e4m3 values of K per lane
   static constexpr int mfma_per_block = 1;
+  using acc_t = f32x16_t;
   // v_mfma_f32_32x32x64_f8f6f4 with both formats e4m3 and no block scaling: lane l supplies row
   // l % 32 and the 32 consecutive K values (l / 32) * 32 ... of a 64-wide K block (checked on
   // gfx950 against an integer reference); the accumulator layout is that of the other 32x32 forms.
@@ -132,21 +151,26 @@ struct GemmTile {
   static constexpr int NWAVES = WGM * WGN;
   static constexpr int NT = 64 * NWAVES;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
-  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int NB = Elem<E>::block;           // edge of an MFMA block
+  static constexpr int LG = 64 / NB;                  // lane groups of a block (each holds other K chunks / rows)
+  static constexpr int VB = NB * NB / 64;             // accumulator values per lane and block
+  static constexpr int TM = WM / NB, TN = WN / NB;
   static constexpr int KB = 128;                      // bytes of K per row per step (a cache line)
   static constexpr int FC = Elem<E>::frag_chunks;     // 16-byte chunks per lane and fragment
-  static constexpr int NSUB = KB / 32 / FC;           // K sub-steps (one fragment pair each)
+  static constexpr int NSUB = KB / 16 / (LG * FC);    // K sub-steps (one fragment pair each)
   static constexpr int NSLOT = 5;                     // ring of operand-tile slots
   static constexpr int SLOT = (BM > BN ? BM : BN) * KB;
   static constexpr int LDS_BYTES = NSLOT * SLOT;
   static constexpr int A_LD = BM / 8 / NWAVES;        // direct-to-LDS load instructions per wave
   static constexpr int B_LD = BN / 8 / NWAVES;        // per K-step (each moves 8 rows)
   static constexpr int LOADS_PER_STEP = A_LD + B_LD;
-  static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tiles are 32x32 blocks");
+  static_assert(BM % (WGM * NB) == 0 && BN % (WGN * NB) == 0, "wave tiles are made of MFMA blocks");
+  static_assert(NB == 32 || NB == 16, "block edge");
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile loads divide evenly");
   static_assert(NSUB % 2 == 0, "fragment double-buffering assumes an even number of sub-steps");
 
-  using Acc = f32x16_t[TM][TN];
+  using Block = typename Elem<E>::acc_t;
+  using Acc = Block[TM][TN];
 
   __device__ static inline int lane() { return threadIdx.x & 63; }
   __device__ static inline int wave() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
@@ -156,9 +180,11 @@ struct GemmTile {
   __device__ static inline int m_of(int i, int v) { return m_base() + m_const(i, v); }
   // m_of split into its lane-dependent part and a compile-time constant, so that comparisons
   // against it can be written with immediates instead of one live register per (i, v)
-  __device__ static inline int m_base() { return wave_m() * WM + 4 * (lane() >> 5); }
-  __device__ static constexpr int m_const(int i, int v) { return i * 32 + 8 * (v >> 2) + (v & 3); }
-  __device__ static inline int n_of(int j) { return wave_n() * WN + j * 32 + (lane() & 31); }
+  __device__ static inline int m_base() { return wave_m() * WM + 4 * (lane() / NB); }
+  __device__ static constexpr int m_const(int i, int v) {
+    return NB == 32 ? i * 32 + 8 * (v >> 2) + (v & 3) : i * 16 + v;
+  }
+  __device__ static inline int n_of(int j) { return wave_n() * WN + j * NB + (lane() % NB); }
 
   __device__ static inline int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
@@ -174,7 +200,7 @@ struct GemmTile {
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int v = 0; v < VB; ++v) acc[i][j][v] = 0.f;
   }
 
   // acc += A_tile * B_tile^T over `ksteps` steps of 128 bytes.
@@ -206,9 +232,9 @@ struct GemmTile {
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int w = wave();
     const int l = lane();
-    const int half = l >> 5;
-    const int rA0 = wave_m() * WM + (l & 31);
-    const int rB0 = wave_n() * WN + (l & 31);
+    const int grp = l / NB;
+    const int rA0 = wave_m() * WM + (l % NB);
+    const int rB0 = wave_n() * WN + (l % NB);
 
     // Loads of one operand tile for K-step ks into ring slot `slot`; `part` selects which of
     // the NPART groups of this wave's load instructions to issue.
@@ -247,10 +273,10 @@ struct GemmTile {
     auto read_a = [&](const char* sa, int s, int buf) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int r = rA0 + i * 32;
+        const int r = rA0 + i * NB;
 #pragma unroll
         for (int c = 0; c < FC; ++c) {
-          const int ch = (2 * s + half) * FC + c;
+          const int ch = (LG * s + grp) * FC + c;
           fa[buf][i][c] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + ((ch ^ swz(r)) << 4));
         }
       }
@@ -258,10 +284,10 @@ struct GemmTile {
     auto read_b = [&](const char* sb, int s, int buf) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int r = rB0 + j * 32;
+        const int r = rB0 + j * NB;
 #pragma unroll
         for (int c = 0; c < FC; ++c) {
-          const int ch = (2 * s + half) * FC + c;
+          const int ch = (LG * s + grp) * FC + c;
           fb[buf][j][c] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + ((ch ^ swz(r)) << 4));
         }
       }
@@ -405,9 +431,114 @@ struct GemmTile {
         sA = sA1;
         sB = sB1;
       }
+    } else if constexpr (NB == 16) {
+      // bf16 on 16x16x32 blocks: two sub-steps per K-step, four lane groups with one chunk each.  Same
+      // ring and the same four regions per K-step as below (32 MFMAs, eight fragment reads, four loads
+      // each; hand-over barrier in the middle of the K-step), but the MFMAs are asm statements, so
+      // the interleave is written out: behind each of the first eight MFMAs of a region one fragment
+      // read, then one load behind every sixth MFMA, each step pinned by a scheduling barrier (an MFMA
+      // of this form issues every 16 cycles, which leaves room for about three other instructions).
+      static_assert(NSUB == 2 && FC == 1 && TM == TN && TM % 2 == 0, "two regions per sub-step");
+      constexpr int RMMAS = TM * TN / 2;     // MFMAs per region
+      constexpr int RREADS = TM;             // fragment reads per region
+      static_assert(RREADS + LD_REGION <= RMMAS, "region pattern");
+      auto read_a1 = [&](const char* sa, int sub, int buf, int i) {
+        const int r = rA0 + i * NB;
+        fa[buf][i][0] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + (((LG * sub + grp) ^ swz(r)) << 4));
+      };
+      auto read_b1 = [&](const char* sb, int sub, int buf, int j) {
+        const int r = rB0 + j * NB;
+        fb[buf][j][0] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + (((LG * sub + grp) ^ swz(r)) << 4));
+      };
+      auto issue_a1 = [&](int ks, int slot, int q) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(lds + slot * SLOT + (w * A_LD + q) * 1024), 16, offA[q],
+                                                 ks * KB, 0, 0);
+      };
+      auto issue_b1 = [&](int ks, int slot, int q) {
+        uint32_t vo = offB[q];
+        if constexpr (kMaskB) vo = (ks * KB < limB[q]) ? vo : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(lds + slot * SLOT + (w * B_LD + q) * 1024), 16, vo,
+                                                 ks * KB, 0, 0);
+      };
+      // One region: the MFMAs of row blocks [i0, i0 + TM/2) on fragment set `buf`, with the reads of
+      // operand `rx` (true: X) for (slot base `src`, sub-step `sub`) into set `rbuf`, and, when `ld`,
+      // the loads [q0, q0 + LD_REGION) of operand `lx` for K-step `lks` into ring slot `lslot`.
+      auto region = [&](int buf, int i0, bool rd, bool rx, const char* src, int sub, int rbuf, bool ld, bool lx, int lks,
+                        int lslot, int q0) {
+        constexpr int kGap = (RMMAS - RREADS) / LD_REGION;
+#pragma unroll
+        for (int idx = 0; idx < RMMAS; ++idx) {
+          const int i = i0 + idx / TN, j = idx % TN;
+          Elem<E>::mma(acc[i][j], fa[buf][i], fb[buf][j]);
+          if (rd && idx < RREADS) {
+            if (rx == !kLeadB) read_a1(src, sub, rbuf, idx); else read_b1(src, sub, rbuf, idx);
+          }
+          if (ld && idx >= RREADS && (idx - RREADS) % kGap == 0 && (idx - RREADS) / kGap < LD_REGION) {
+            const int q = q0 + (idx - RREADS) / kGap;
+            if (lx == !kLeadB) issue_a1(lks, lslot, q); else issue_b1(lks, lslot, q);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      int sX = 0, sY = 1;
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
+      if (ksteps > 1) {
+        issue_x(1, 2, 0); issue_x(1, 2, 1);
+        issue_y(1, 3, 0); issue_y(1, 3, 1);
+        __builtin_amdgcn_s_waitcnt(wait_vm(2 * A_LD));
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      }
+      __builtin_amdgcn_s_barrier();
+      frags_xy(lds + sX * SLOT, lds + sY * SLOT, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      int ks = 0;
+      // Entering K-step ks: X(ks), Y(ks) landed, X(ks+1), Y(ks+1) resident or in flight; the slot of
+      // Y(ks-1) is free (the barrier in the middle of K-step ks-1).
+      for (; ks + 2 < ksteps; ++ks) {
+        const char* cx = lds + sX * SLOT;
+        const char* cy = lds + sY * SLOT;
+        const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
+        const int sX2 = next_slot(sX1, 2);   // slot of X(ks+2) == slot of Y(ks-1)
+        const int sY2 = sX;                  // slot of Y(ks+2) == slot of X(ks)
+        region(0, 0, true, true, cx, 1, 1, true, true, ks + 2, sX2, 0);
+        region(0, TM / 2, true, false, cy, 1, 1, true, true, ks + 2, sX2, LD_REGION);
+        // hand-over: everything but X(ks+2) has landed, i.e. X(ks+1) and Y(ks+1) are complete
+        __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        region(1, 0, true, true, lds + sX1 * SLOT, 0, 0, true, false, ks + 2, sY2, 0);
+        region(1, TM / 2, true, false, lds + sY1 * SLOT, 0, 0, true, false, ks + 2, sY2, LD_REGION);
+        sX = sX1;
+        sY = sY1;
+      }
+      // drain: the last two K-steps (their tiles were all requested above or in the prologue)
+      for (; ks < ksteps; ++ks) {
+        const char* cx = lds + sX * SLOT;
+        const char* cy = lds + sY * SLOT;
+        const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
+        const bool more = ks + 1 < ksteps;
+        region(0, 0, true, true, cx, 1, 1, false, false, 0, 0, 0);
+        region(0, TM / 2, true, false, cy, 1, 1, false, false, 0, 0, 0);
+        region(1, 0, false, false, cx, 0, 0, false, false, 0, 0, 0);
+        if (more) {
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
+          __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          frags_xy(lds + sX1 * SLOT, lds + sY1 * SLOT, 0, 0);
+        }
+        region(1, TM / 2, false, false, cx, 0, 0, false, false, 0, 0, 0);
+        sX = sX1;
+        sY = sY1;
+      }
+      // the asm MFMAs' results are read by ordinary instructions next: let the last ones retire
+      asm volatile("s_nop 15\n\ts_nop 15");
     } else {
-      // Two sub-steps per K-step (8-bit operands: an MFMA consumes 64 values of K, a sub-step two
-      // 16-byte chunks per lane and operand).  Same ring, shifted by a quarter step so that the
+      // Two sub-steps per K-step (bf16 on 16x16x32 blocks: four lane groups with one chunk each; 8-bit
+      // operands: an MFMA consumes 64 values of K, two chunks per lane).  Same ring, shifted by a quarter step so that the
       // work still falls into four equal regions of TM*TN/2 MFMAs, eight fragment reads and half a
       // tile of loads each: the hand-over barrier sits in the middle of the K-step; after it a wave
       // reads the first fragments of K-step ks+1 and issues Y(ks+2) into the slot of X(ks), which that
@@ -421,13 +552,17 @@ struct GemmTile {
       };
       constexpr int RMMAS = TM * TN / 2;     // MFMAs per region
       constexpr int RREADS = TM * FC;        // fragment reads per region (TM == TN)
-      static_assert(TM == TN && RREADS == RMMAS && LD_REGION <= RMMAS / 2, "region pattern");
+      static_assert(TM == TN && RREADS % 2 == 0 && RREADS / 2 + LD_REGION <= RMMAS, "region pattern");
+      // behind each of the first MFMAs of a region two fragment reads, then one load behind every
+      // kGap-th MFMA of the rest
       auto sched_half = [&](bool loads) {
+        constexpr int kGap = (RMMAS - RREADS / 2) / LD_REGION;
 #pragma unroll
         for (int i = 0; i < RMMAS; ++i) {
           __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-          if (i < RMMAS / 2) __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
-          if (loads && i >= RMMAS / 2 && i - RMMAS / 2 < LD_REGION) __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
+          if (i < RREADS / 2) __builtin_amdgcn_sched_group_barrier(kDsRead, 2, 0);
+          if (loads && i >= RREADS / 2 && (i - RREADS / 2) % kGap == 0 && (i - RREADS / 2) / kGap < LD_REGION)
+            __builtin_amdgcn_sched_group_barrier(kVmem, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       };

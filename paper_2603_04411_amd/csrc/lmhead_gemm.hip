@@ -121,7 +121,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
+          for (int v = 0; v < G::VB; ++v) {
             const bool eq = relj[j] == G::m_const(i, v);
             zsel = eq ? acc[i][j][v] : zsel;
             found |= eq;
@@ -131,20 +131,28 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
   }
 
-  // softmax statistics of this tile, inside the lane, one 32x32 block (16 values of one token
-  // column) at a time; the scheduling barrier after each block keeps the accumulator reads of
-  // later blocks from being hoisted, so only 16 values are live in VGPRs at a time
+  // softmax statistics of this tile, inside the lane, 16 values of one token column at a time (one
+  // 32x32 block or four 16x16 blocks); the scheduling barrier after each group keeps the
+  // accumulator reads of later groups from being hoisted, so only 16 values are live in VGPRs at a time
   {
     const int vlim = a.V - m0 - G::m_base();   // vocabulary rows with m_const >= vlim are padding
     // logit = accumulator * zscale (zscale = 1 unless the operands are scaled 8-bit copies); the factor
-    // is folded into the constants of the block instead of being applied per element
+    // is folded into the constants of the group instead of being applied per element
     const float zscale = a.zscale;
     const float kz = kLog2e * zscale;
-    auto block_stats = [&](auto full_tag, const f32x16_t& blk, int i, float& m_run, float& s_run, float& t_run) {
+    constexpr int BPC = 16 / G::VB;            // blocks per group of 16 values
+    static_assert(G::TM % BPC == 0, "groups of 16 values");
+    auto group_stats = [&](auto full_tag, int ic, int j, float& m_run, float& s_run, float& t_run) {
       constexpr bool kFull = decltype(full_tag)::value;
       float z[16];
+      bool ok[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) z[v] = (kFull || G::m_const(i, v) < vlim) ? blk[v] : kNegInf;
+      for (int b = 0; b < BPC; ++b)
+#pragma unroll
+        for (int v = 0; v < G::VB; ++v) {
+          ok[b * G::VB + v] = kFull || G::m_const(ic * BPC + b, v) < vlim;
+          z[b * G::VB + v] = ok[b * G::VB + v] ? acc[ic * BPC + b][j][v] : kNegInf;
+        }
       float tmax = fmaxf(z[0], z[1]);
 #pragma unroll
       for (int v = 2; v < 16; v += 2) tmax = fmaxf(tmax, fmaxf(z[v], z[v + 1]));
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       for (int v = 0; v < 16; ++v) {
         const float e = fast_exp2(fmaf(z[v], kz, bias));   // exp2(-inf) = 0 on padding rows
         ss += e;
-        ts = fmaf(e, (kFull || G::m_const(i, v) < vlim) ? z[v] : 0.f, ts);
+        ts = fmaf(e, ok[v] ? z[v] : 0.f, ts);
       }
       s_run = fmaf(s_run, sc, ss);
       t_run = fmaf(t_run, sc, ts * zscale);
@@ -168,24 +176,27 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 #pragma unroll
       for (int j = 0; j < G::TN; ++j)
 #pragma unroll
-        for (int i = 0; i < G::TM; ++i) block_stats(std::true_type{}, acc[i][j], i, mr[j], sr[j], tr[j]);
+        for (int ic = 0; ic < G::TM / BPC; ++ic) group_stats(std::true_type{}, ic, j, mr[j], sr[j], tr[j]);
     } else {
 #pragma unroll
       for (int j = 0; j < G::TN; ++j)
 #pragma unroll
-        for (int i = 0; i < G::TM; ++i) block_stats(std::false_type{}, acc[i][j], i, mr[j], sr[j], tr[j]);
+        for (int ic = 0; ic < G::TM / BPC; ++ic) group_stats(std::false_type{}, ic, j, mr[j], sr[j], tr[j]);
     }
   }
 
-  // combine the two half-waves (same token, other vocabulary rows), then the WGM waves via LDS
+  // combine the lane groups of a block (same token, other vocabulary rows), then the WGM waves via LDS
   float* red = reinterpret_cast<float*>(smem);  // [WGM][BN][3]
 #pragma unroll
   for (int j = 0; j < G::TN; ++j) {
-    const float m2 = __shfl_xor(mr[j], 32);
-    const float s2 = __shfl_xor(sr[j], 32);
-    const float t2 = __shfl_xor(tr[j], 32);
-    merge_stats(mr[j], sr[j], tr[j], m2, s2, t2);
-    if (G::lane() < 32) {
+#pragma unroll
+    for (int o = 32; o >= G::NB; o >>= 1) {
+      const float m2 = __shfl_xor(mr[j], o);
+      const float s2 = __shfl_xor(sr[j], o);
+      const float t2 = __shfl_xor(tr[j], o);
+      merge_stats(mr[j], sr[j], tr[j], m2, s2, t2);
+    }
+    if (G::lane() < G::NB) {
       float* q = red + ((size_t)G::wave_m() * G::BN + G::n_of(j)) * 3;
       q[0] = mr[j];
       q[1] = sr[j];
@@ -282,8 +293,8 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   // is neither orientation's row.  JG of the wave's TN token blocks are staged per phase (as many
   // as fit next to each other in LDS in both orientations).
   constexpr int ESZ = Elem<EO>::size;
-  constexpr int JG = ESZ == 2 ? 2 : 1;            // token blocks (of 32) per wave per phase
-  constexpr int NTOK = G::WGN * JG * 32;          // tokens staged per phase
+  constexpr int JG = (ESZ == 2 ? 64 : 32) / G::NB;   // token blocks per wave per phase
+  constexpr int NTOK = G::WGN * JG * G::NB;       // tokens staged per phase
   constexpr int P1 = G::BM * ESZ + 16;            // pitch of the [token][vocab] staging rows
   constexpr int P2 = NTOK * ESZ + 16;             // pitch of the [vocab][token] staging rows
   constexpr int L2_OFF = NTOK * P1;
@@ -304,14 +315,14 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
       const float g = gj[j];
       const float bias = biasj[j];
       const int rel = relj[j];
-      const int tl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);   // token within the phase
+      const int tl = G::wave_n() * (JG * G::NB) + jj * G::NB + (G::lane() % G::NB);   // token within the phase
       auto emit = [&](auto plain_tag) {
         constexpr bool kPlain = decltype(plain_tag)::value;
         const float ng = -g;
 #pragma unroll
         for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; q < G::VB / 4; ++q) {
             float dz[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -343,7 +354,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 #pragma unroll
       for (int r0 = 0; r0 < NTOK; r0 += RPP) {
         const int tl = r0 + threadIdx.x / CPR;
-        const int nl = (tl / (JG * 32)) * G::WN + jg * (JG * 32) + tl % (JG * 32);   // token within the tile
+        const int nl = (tl / (JG * G::NB)) * G::WN + jg * (JG * G::NB) + tl % (JG * G::NB);   // token within the tile
         const u32x4_t v = *reinterpret_cast<const u32x4_t*>(st1 + tl * P1 + c * 16);
         *reinterpret_cast<u32x4_t*>(dZ + ((size_t)(n0 + nl) * a.ldZ + mrel0) * ESZ + c * 16) = v;
       }
@@ -355,7 +366,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
       constexpr int TPC = 16 / ESZ;           // tokens per 16-byte chunk
       const int c = threadIdx.x % CPR;
       const int tl = c * TPC;
-      const int nl = (tl / (JG * 32)) * G::WN + jg * (JG * 32) + tl % (JG * 32);
+      const int nl = (tl / (JG * G::NB)) * G::WN + jg * (JG * G::NB) + tl % (JG * G::NB);
 #pragma unroll
       for (int r0 = 0; r0 < G::BM; r0 += RPP) {
         const int m = r0 + threadIdx.x / CPR;
@@ -407,15 +418,15 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   // The wave streams out tile columns (output rows) wave, wave + 4, ... of each phase of the epilogue.
   // Lane 32 p + i fetches the output row of iteration i of phase p now; the epilogue reads it with
   // readlane instead of one dependent global load per row.
-  constexpr int JG = 2;                           // column blocks (of 32) per wave per phase
-  constexpr int NCOL = G::WGN * JG * 32;          // tile columns (n) staged per phase
+  constexpr int JG = 64 / G::NB;                  // column blocks per wave per phase (64 columns)
+  constexpr int NCOL = G::WGN * JG * G::NB;       // tile columns (n) staged per phase
   constexpr int ROWS_PER_WAVE = NCOL / G::NWAVES; // per phase
   static_assert(ROWS_PER_WAVE * (G::TN / JG) == 64, "one output row index per lane");
   int my_row;
   {
     const int p = G::lane() / ROWS_PER_WAVE, i = G::lane() % ROWS_PER_WAVE;
     const int r = G::wave() + G::NWAVES * i;
-    const int64_t n = n0 + (r / (JG * 32)) * G::WN + p * (JG * 32) + r % (JG * 32);
+    const int64_t n = n0 + (r / (JG * G::NB)) * G::WN + p * (JG * G::NB) + r % (JG * G::NB);
     int64_t row = -1;
     if (n < n_lim) row = a.part ? n : (a.rowmap ? (int64_t)a.rowmap[n] : a.row_base + n);
     my_row = (int)row;
@@ -444,11 +455,11 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj) {
       const int j = jg * JG + jj;
-      const int nl = G::wave_n() * (JG * 32) + jj * 32 + (G::lane() & 31);
+      const int nl = G::wave_n() * (JG * G::NB) + jj * G::NB + (G::lane() % G::NB);
 #pragma unroll
       for (int i = 0; i < G::TM; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < G::VB / 4; ++q) {
           const f32x4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
           *reinterpret_cast<f32x4_t*>(smem + nl * P + G::m_of(i, 4 * q) * 4) = v;
         }
