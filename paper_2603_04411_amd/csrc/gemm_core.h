@@ -22,10 +22,10 @@
 // One workgroup barrier per K-step; a unit is complete when each wave's own vmcnt has
 // drained past it (loads retire in order) and all waves have passed that barrier.
 //
-// LDS slot layout: 256 rows of 128 bytes (eight 16-byte chunks); chunk c
-// of row r sits at chunk position c ^ swz(r).  A direct-to-LDS load writes lane L's 16
-// bytes at wave_base + 16 L, i.e. row L/8, position L%8 of an 8-row group, so lane L
-// simply fetches the global chunk (L%8) ^ swz(row).
+// LDS slot layout: 256 rows of 128 bytes (eight 16-byte chunks); chunk c of row r sits at chunk
+// position c ^ swz(r) of its row, and the rows of the five slots are interleaved by groups of 8
+// (see GSTR below).  A direct-to-LDS load writes lane L's 16 bytes at wave_base + 16 L, i.e. row
+// L/8, position L%8 of an 8-row group, so lane L simply fetches the global chunk (L%8) ^ swz(row).
 //
 // Fragment layout used for both operands (what matters is only that A and B agree): the wave tile
 // is cut into NB x NB MFMA blocks; lane l of a block holds row l % NB and, in K sub-step s, the
@@ -161,6 +161,12 @@ struct GemmTile {
   static constexpr int NSLOT = 5;                     // ring of operand-tile slots
   static constexpr int SLOT = (BM > BN ? BM : BN) * KB;
   static constexpr int LDS_BYTES = NSLOT * SLOT;
+  // The slots are interleaved in LDS by groups of 8 rows (1 KB, what one load instruction writes):
+  // group g of slot s sits at (g * NSLOT + s) KB.  A fragment's address is then a lane-dependent part
+  // that does not depend on the slot plus s KB, which fits the DS instructions' immediate offset.
+  static constexpr int SSTR = 8 * KB;                 // from a slot to the next, within a row group
+  static constexpr int GSTR = NSLOT * SSTR;           // from a row group to the next
+  __device__ static inline int row_off(int r) { return (r >> 3) * GSTR + (r & 7) * KB; }
   static constexpr int A_LD = BM / 8 / NWAVES;        // direct-to-LDS load instructions per wave
   static constexpr int B_LD = BN / 8 / NWAVES;        // per K-step (each moves 8 rows)
   static constexpr int LOADS_PER_STEP = A_LD + B_LD;
@@ -254,18 +260,18 @@ struct GemmTile {
     const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
         uniform_ptr(B), 0, (int)__builtin_amdgcn_readfirstlane(bytesB), 0x00020000);
     auto issue_a = [&](int ks, int slot, int part) {
-      char* st = lds + slot * SLOT;
+      char* st = lds + slot * SSTR;
 #pragma unroll
       for (int q = part * (A_LD / NPART); q < (part + 1) * (A_LD / NPART); ++q)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(st + (w * A_LD + q) * 1024), 16, offA[q], ks * KB, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(st + (w * A_LD + q) * GSTR), 16, offA[q], ks * KB, 0, 0);
     };
     auto issue_b = [&](int ks, int slot, int part) {
-      char* st = lds + slot * SLOT;
+      char* st = lds + slot * SSTR;
 #pragma unroll
       for (int q = part * (B_LD / NPART); q < (part + 1) * (B_LD / NPART); ++q) {
         uint32_t vo = offB[q];
         if constexpr (kMaskB) vo = (ks * KB < limB[q]) ? vo : 0x80000000u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(st + (w * B_LD + q) * 1024), 16, vo, ks * KB, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(st + (w * B_LD + q) * GSTR), 16, vo, ks * KB, 0, 0);
       }
     };
 
@@ -277,7 +283,7 @@ struct GemmTile {
 #pragma unroll
         for (int c = 0; c < FC; ++c) {
           const int ch = (LG * s + grp) * FC + c;
-          fa[buf][i][c] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + ((ch ^ swz(r)) << 4));
+          fa[buf][i][c] = *reinterpret_cast<const u32x4_t*>(sa + row_off(r) + ((ch ^ swz(r)) << 4));
         }
       }
     };
@@ -288,7 +294,7 @@ struct GemmTile {
 #pragma unroll
         for (int c = 0; c < FC; ++c) {
           const int ch = (LG * s + grp) * FC + c;
-          fb[buf][j][c] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + ((ch ^ swz(r)) << 4));
+          fb[buf][j][c] = *reinterpret_cast<const u32x4_t*>(sb + row_off(r) + ((ch ^ swz(r)) << 4));
         }
       }
     };
@@ -361,7 +367,7 @@ struct GemmTile {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
       }
       __builtin_amdgcn_s_barrier();
-      frags_xy(lds + sA * SLOT, lds + sB * SLOT, 0, 0);
+      frags_xy(lds + sA * SSTR, lds + sB * SSTR, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
       // Steady state.  Entering K-step ks: X(ks), Y(ks), X(ks+1) and the first half of Y(ks+1) are
@@ -369,8 +375,8 @@ struct GemmTile {
       // frees the slots of X(ks) and Y(ks), and the first of them is put to use at once (Y(ks+2)),
       // so no slot is ever idle: Y has half a K-step to a whole one to land, X one to one and a half.
       for (; ks + 2 < ksteps; ++ks) {
-        const char* ca = lds + sA * SLOT;
-        const char* cb = lds + sB * SLOT;
+        const char* ca = lds + sA * SSTR;
+        const char* cb = lds + sB * SSTR;
         const int sB1 = next_slot(sB, 2);   // slot of Y(ks+1) == slot of X(ks-1)
         const int sA1 = next_slot(sA, 2);   // slot of X(ks+1)
         const int sA2 = next_slot(sA1, 2);  // slot of X(ks+2) == slot of Y(ks-1)
@@ -395,7 +401,7 @@ struct GemmTile {
         __builtin_amdgcn_sched_barrier(0);
         // sub-step 3 overlaps the first fragment reads of K-step ks+1 and the first half of Y(ks+2),
         // which goes into the slot of X(ks) that this barrier has just freed
-        frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+        frags_xy(lds + sA1 * SSTR, lds + sB1 * SSTR, 0, 0);
         issue_y(ks + 2, sA, 0);
         mma_all(1);
         sched_region(LD_REGION_B);
@@ -404,8 +410,8 @@ struct GemmTile {
       }
       // drain: the last two K-steps (the first half of Y(ks+1) is already under way)
       for (; ks < ksteps; ++ks) {
-        const char* ca = lds + sA * SLOT;
-        const char* cb = lds + sB * SLOT;
+        const char* ca = lds + sA * SSTR;
+        const char* cb = lds + sB * SSTR;
         const int sB1 = next_slot(sB, 2);
         const int sA1 = next_slot(sA, 2);
         const bool more = ks + 1 < ksteps;
@@ -424,7 +430,7 @@ struct GemmTile {
           __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          frags_xy(lds + sA1 * SLOT, lds + sB1 * SLOT, 0, 0);
+          frags_xy(lds + sA1 * SSTR, lds + sB1 * SSTR, 0, 0);
         }
         mma_all(1);
         __builtin_amdgcn_sched_barrier(0);
@@ -444,20 +450,20 @@ struct GemmTile {
       static_assert(RREADS + LD_REGION <= RMMAS, "region pattern");
       auto read_a1 = [&](const char* sa, int sub, int buf, int i) {
         const int r = rA0 + i * NB;
-        fa[buf][i][0] = *reinterpret_cast<const u32x4_t*>(sa + r * KB + (((LG * sub + grp) ^ swz(r)) << 4));
+        fa[buf][i][0] = *reinterpret_cast<const u32x4_t*>(sa + row_off(r) + (((LG * sub + grp) ^ swz(r)) << 4));
       };
       auto read_b1 = [&](const char* sb, int sub, int buf, int j) {
         const int r = rB0 + j * NB;
-        fb[buf][j][0] = *reinterpret_cast<const u32x4_t*>(sb + r * KB + (((LG * sub + grp) ^ swz(r)) << 4));
+        fb[buf][j][0] = *reinterpret_cast<const u32x4_t*>(sb + row_off(r) + (((LG * sub + grp) ^ swz(r)) << 4));
       };
       auto issue_a1 = [&](int ks, int slot, int q) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(lds + slot * SLOT + (w * A_LD + q) * 1024), 16, offA[q],
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(lds + slot * SSTR + (w * A_LD + q) * GSTR), 16, offA[q],
                                                  ks * KB, 0, 0);
       };
       auto issue_b1 = [&](int ks, int slot, int q) {
         uint32_t vo = offB[q];
         if constexpr (kMaskB) vo = (ks * KB < limB[q]) ? vo : 0x80000000u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(lds + slot * SLOT + (w * B_LD + q) * 1024), 16, vo,
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(lds + slot * SSTR + (w * B_LD + q) * GSTR), 16, vo,
                                                  ks * KB, 0, 0);
       };
       // One region: the MFMAs of row blocks [i0, i0 + TM/2) on fragment set `buf`, with the reads of
@@ -491,33 +497,48 @@ struct GemmTile {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
       }
       __builtin_amdgcn_s_barrier();
-      frags_xy(lds + sX * SLOT, lds + sY * SLOT, 0, 0);
+      frags_xy(lds + sX * SSTR, lds + sY * SSTR, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
-      // Entering K-step ks: X(ks), Y(ks) landed, X(ks+1), Y(ks+1) resident or in flight; the slot of
-      // Y(ks-1) is free (the barrier in the middle of K-step ks-1).
-      for (; ks + 2 < ksteps; ++ks) {
-        const char* cx = lds + sX * SLOT;
-        const char* cy = lds + sY * SLOT;
-        const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
+      // One steady-state K-step with X(ks), Y(ks) in slots sx, sy.  Entering it: X(ks), Y(ks) landed,
+      // X(ks+1), Y(ks+1) resident or in flight; the slot of Y(ks-1) is free (the barrier in the middle
+      // of K-step ks-1).
+      auto kstep = [&](int ks_, int sx, int sy) {
+        const char* cx = lds + sx * SSTR;
+        const char* cy = lds + sy * SSTR;
+        const int sX1 = next_slot(sx, 2), sY1 = next_slot(sy, 2);
         const int sX2 = next_slot(sX1, 2);   // slot of X(ks+2) == slot of Y(ks-1)
-        const int sY2 = sX;                  // slot of Y(ks+2) == slot of X(ks)
-        region(0, 0, true, true, cx, 1, 1, true, true, ks + 2, sX2, 0);
-        region(0, TM / 2, true, false, cy, 1, 1, true, true, ks + 2, sX2, LD_REGION);
+        const int sY2 = sx;                  // slot of Y(ks+2) == slot of X(ks)
+        region(0, 0, true, true, cx, 1, 1, true, true, ks_ + 2, sX2, 0);
+        region(0, TM / 2, true, false, cy, 1, 1, true, true, ks_ + 2, sX2, LD_REGION);
         // hand-over: everything but X(ks+2) has landed, i.e. X(ks+1) and Y(ks+1) are complete
         __builtin_amdgcn_s_waitcnt(wait_vm(A_LD));
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        region(1, 0, true, true, lds + sX1 * SLOT, 0, 0, true, false, ks + 2, sY2, 0);
-        region(1, TM / 2, true, false, lds + sY1 * SLOT, 0, 0, true, false, ks + 2, sY2, LD_REGION);
-        sX = sX1;
-        sY = sY1;
+        region(1, 0, true, true, lds + sX1 * SSTR, 0, 0, true, false, ks_ + 2, sY2, 0);
+        region(1, TM / 2, true, false, lds + sY1 * SSTR, 0, 0, true, false, ks_ + 2, sY2, LD_REGION);
+      };
+      // The ring returns to its starting state every NSLOT K-steps: unrolled by that many, every slot
+      // number is a constant, and with the interleaved slot layout a fragment's LDS address is a
+      // loop-invariant register plus an immediate (no address arithmetic left in the loop).
+      static_assert(NSLOT == 5, "unrolled by the ring's period");
+      for (; ks + 2 + (NSLOT - 1) < ksteps; ks += NSLOT) {
+        kstep(ks, 0, 1);
+        kstep(ks + 1, 2, 3);
+        kstep(ks + 2, 4, 0);
+        kstep(ks + 3, 1, 2);
+        kstep(ks + 4, 3, 4);
+      }
+      for (; ks + 2 < ksteps; ++ks) {
+        kstep(ks, sX, sY);
+        sX = next_slot(sX, 2);
+        sY = next_slot(sY, 2);
       }
       // drain: the last two K-steps (their tiles were all requested above or in the prologue)
       for (; ks < ksteps; ++ks) {
-        const char* cx = lds + sX * SLOT;
-        const char* cy = lds + sY * SLOT;
+        const char* cx = lds + sX * SSTR;
+        const char* cy = lds + sY * SSTR;
         const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
         const bool more = ks + 1 < ksteps;
         region(0, 0, true, true, cx, 1, 1, false, false, 0, 0, 0);
@@ -528,7 +549,7 @@ struct GemmTile {
           __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          frags_xy(lds + sX1 * SLOT, lds + sY1 * SLOT, 0, 0);
+          frags_xy(lds + sX1 * SSTR, lds + sY1 * SSTR, 0, 0);
         }
         region(1, TM / 2, false, false, cx, 0, 0, false, false, 0, 0, 0);
         sX = sX1;
@@ -577,14 +598,14 @@ struct GemmTile {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
       }
       __builtin_amdgcn_s_barrier();
-      frags_xy(lds + sX * SLOT, lds + sY * SLOT, 0, 0);
+      frags_xy(lds + sX * SSTR, lds + sY * SSTR, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
       // Entering K-step ks: X(ks), Y(ks) landed, X(ks+1), Y(ks+1) resident or in flight; the slot of
       // Y(ks-1) is free (the barrier in the middle of K-step ks-1).
       for (; ks + 2 < ksteps; ++ks) {
-        const char* cx = lds + sX * SLOT;
-        const char* cy = lds + sY * SLOT;
+        const char* cx = lds + sX * SSTR;
+        const char* cy = lds + sY * SSTR;
         const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
         const int sX2 = next_slot(sX1, 2);   // slot of X(ks+2) == slot of Y(ks-1)
         const int sY2 = sX;                  // slot of Y(ks+2) == slot of X(ks)
@@ -601,11 +622,11 @@ struct GemmTile {
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_x(lds + sX1 * SLOT, 0, 0);
+        read_x(lds + sX1 * SSTR, 0, 0);
         issue_y(ks + 2, sY2, 0);
         mma_rows(1, 0, TM / 2);
         sched_half(true);
-        read_y(lds + sY1 * SLOT, 0, 0);
+        read_y(lds + sY1 * SSTR, 0, 0);
         issue_y(ks + 2, sY2, 1);
         mma_rows(1, TM / 2, TM);
         sched_half(true);
@@ -614,8 +635,8 @@ struct GemmTile {
       }
       // drain: the last two K-steps (their tiles were all requested above or in the prologue)
       for (; ks < ksteps; ++ks) {
-        const char* cx = lds + sX * SLOT;
-        const char* cy = lds + sY * SLOT;
+        const char* cx = lds + sX * SSTR;
+        const char* cy = lds + sY * SSTR;
         const int sX1 = next_slot(sX, 2), sY1 = next_slot(sY, 2);
         const bool more = ks + 1 < ksteps;
         read_x(cx, 1, 1);
@@ -629,7 +650,7 @@ struct GemmTile {
           __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          frags_xy(lds + sX1 * SLOT, lds + sY1 * SLOT, 0, 0);
+          frags_xy(lds + sX1 * SSTR, lds + sY1 * SSTR, 0, 0);
         }
         mma_rows(1, 0, TM);
         __builtin_amdgcn_sched_barrier(0);
