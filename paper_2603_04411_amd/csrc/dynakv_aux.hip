@@ -546,7 +546,7 @@ __global__ __launch_bounds__(1024) void kv_scan_blocks_kernel(int64_t* __restric
     const int64_t x = i < nblocks ? blocksum[i] : 0;
     buf[threadIdx.x] = x;
     __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
+    for (unsigned o = 1; o < 1024; o <<= 1) {
       const int64_t y = threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
       __syncthreads();
       buf[threadIdx.x] += y;
@@ -572,7 +572,7 @@ __global__ __launch_bounds__(1024) void kv_scan_offsets_kernel(const int32_t* __
   const int x = i < n ? seg_len(k[i], d, bad) : 0;
   buf[threadIdx.x] = x;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
+  for (unsigned o = 1; o < 1024; o <<= 1) {
     const int y = threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
     __syncthreads();
     buf[threadIdx.x] += y;
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(256) void kv_retain_final_kernel(const double* __re
   sk[threadIdx.x] = a;
   sm[threadIdx.x] = b;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (unsigned o = 128; o > 0; o >>= 1) {
     if (threadIdx.x < o) {
       sk[threadIdx.x] += sk[threadIdx.x + o];
       sm[threadIdx.x] += sm[threadIdx.x + o];

@@ -20,7 +20,6 @@ namespace lmhead {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
