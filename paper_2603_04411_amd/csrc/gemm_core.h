@@ -4,7 +4,7 @@
 // gate logits and ragged reconstruction) are brought to the same form
 // C[m][n] = sum_k A[m][k] * B[n][k]  with both operands K-contiguous.
 // A workgroup owns a BM x BN tile of C; each wavefront owns a (BM/WGM) x (BN/WGN)
-// sub-tile built from 32x32 MFMA blocks.
+// sub-tile built from 16x16 (bf16) or 32x32 (fp32, e4m3) MFMA blocks.
 //
 // Data movement: K is consumed 128 bytes per row per step (64 bf16 or 32 fp32), i.e. one
 // full cache line per row: the vector L1 moves one 128-byte line per ~2 clocks whether or
@@ -12,13 +12,13 @@
 // from global memory straight into LDS (buffer_load_dwordx4 ... lds, no register staging).
 // LDS is a ring of five 32 KB slots, each holding one operand's tile for one K-step; the
 // units A(0) B(0) A(1) B(1) ... (or B first) go round the ring, so besides the two units being
-// multiplied, three are resident or in flight.  The barrier near the end of K-step k frees the
-// slots of A(k) and B(k); a wave issues the loads of B(k+2) into the first of them straight away
-// (last quarter of step k and first quarter of step k+1) and those of A(k+3) into the second
-// during the middle half of step k+1, so no slot is ever idle: B has half a K-step to a whole
-// one to land before the barrier that hands it over, A one to one and a half.  Loads go one
-// behind every fourth MFMA: the vector L1 then never sees a burst (a burst backs up the address
-// queue and blocks the wave's in-order issue, MFMAs included).
+// multiplied, three are resident or in flight.  The hand-over barrier of K-step k (in the middle
+// of the step for the two-sub-step loops, three quarters in for the four-sub-step loop) frees the
+// slots of K-step k's two units, and a wave puts them to use straight away, so no slot is ever
+// idle: the operand that leads the ring has one to one and a half K-steps to land before the
+// barrier that hands it over, the other half a K-step to a whole one.  Loads go one behind every
+// few MFMAs: the vector L1 then never sees a burst (a burst backs up the address queue and blocks
+// the wave's in-order issue, MFMAs included).
 // One workgroup barrier per K-step; a unit is complete when each wave's own vmcnt has
 // drained past it (loads retire in order) and all waves have passed that barrier.
 //
