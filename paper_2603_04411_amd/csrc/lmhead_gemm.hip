@@ -304,9 +304,8 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   char* st2 = smem + L2_OFF;
   const int vlim = a.V - m0 - G::m_base();
   const float kz = kLog2e * a.zscale;              // logit = accumulator * zscale
-  // Most tiles hold no target token of the wave's columns and no padding rows: there dZ = -g p with no
-  // per-element tests.  (Wave-uniform choice.)
-  const bool plain = !__any(hit) && (m0 + G::BM <= a.V);
+  // Which form of the element-wise work this wave needs (wave-uniform, see emit below).
+  const int mode = (m0 + G::BM <= a.V) ? (__any(hit) ? 1 : 0) : 2;
 #pragma unroll
   for (int jg = 0; jg < G::TN / JG; ++jg) {
 #pragma unroll
@@ -316,8 +315,12 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
       const float bias = biasj[j];
       const int rel = relj[j];
       const int tl = G::wave_n() * (JG * G::NB) + jj * G::NB + (G::lane() % G::NB);   // token within the phase
-      auto emit = [&](auto plain_tag) {
-        constexpr bool kPlain = decltype(plain_tag)::value;
+      // mode 0: no target of the wave's columns in this tile, no padding rows: dZ = -g p.
+      // mode 1: a target somewhere in the tile: the one-hot term by a select, still no tests around the
+      //         exponential (about a third of the tiles have such a wave at V = 152 k).
+      // mode 2: the vocabulary's last tile (padding rows give 0).
+      auto emit = [&](auto mode_tag) {
+        constexpr int kMode = decltype(mode_tag)::value;
         const float ng = -g;
 #pragma unroll
         for (int i = 0; i < G::TM; ++i)
@@ -327,8 +330,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float p = fast_exp2(fmaf(acc[i][j][4 * q + e], kz, bias));
-              if constexpr (kPlain) {
+              if constexpr (kMode == 0) {
                 dz[e] = ng * p;
+              } else if constexpr (kMode == 1) {
+                dz[e] = fmaf(ng, p, (G::m_const(i, 4 * q + e) == rel) ? g : 0.f);
               } else {
                 const float oh = (G::m_const(i, 4 * q + e) == rel) ? 1.f : 0.f;
                 dz[e] = (G::m_const(i, 4 * q + e) < vlim) ? g * (oh - p) : 0.f;
@@ -340,10 +345,12 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
             for (int e = 0; e < 4; ++e) Store4<EO>::one(st2 + (mt + e) * P2 + tl * ESZ, dz[e]);
           }
       };
-      if (plain)
-        emit(std::true_type{});
+      if (mode == 0)
+        emit(std::integral_constant<int, 0>{});
+      else if (mode == 1)
+        emit(std::integral_constant<int, 1>{});
       else
-        emit(std::false_type{});
+        emit(std::integral_constant<int, 2>{});
     }
     lds_barrier();
     // [token][vocab] rows -> dZ: one staged row is BM*ESZ contiguous bytes of a dZ row
