@@ -45,7 +45,8 @@ extern "C" {
 
 enum {
   DYNAKV_FLAG_LITERAL_FLIP = 1u << 0, /* Eq. 6 as printed instead of the reverse cumulative sum */
-  DYNAKV_FLAG_ACCUM_GRAD = 1u << 1    /* dynakv_gate_bwd adds to dU, dW, db instead of overwriting them */
+  DYNAKV_FLAG_ACCUM_GRAD = 1u << 1    /* dynakv_gate_bwd adds to dU, dW, db instead of overwriting them
+                                         (the other calls ignore it) */
 };
 
 enum { DYNAKV_GRANULE = 8 }; /* elements; segment offsets in the store are multiples of this */
