@@ -19,8 +19,10 @@
  *    (right padding).  N_v = sum_r len[r].
  *  - Every pointer is DEVICE memory owned by the caller unless it is the
  *    descriptor (host memory).  The library allocates and frees nothing and keeps
- *    no state between calls.  `ws` is scratch: its contents are undefined after
- *    a call, except the sticky error word read by lmhead_check().
+ *    no state between calls (the one exception is the optional benchmark
+ *    instrumentation lmhead_timing_*, which is process-wide).  `ws` is scratch: its
+ *    contents are undefined after a call, except the sticky error word read by
+ *    lmhead_check() and the integer index regions named by lmhead_workspace_region().
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *    work is enqueued on it; calls return without synchronising.  Scalar results
  *    (`loss`) are device scalars.
@@ -51,7 +53,8 @@ extern "C" {
 enum {
   LMHEAD_OK = 0,
   LMHEAD_E_NULL = -1,      /* a required pointer is NULL                              */
-  LMHEAD_E_SHAPE = -2,     /* P,G,T,d,V <= 0; ld < d; d not a multiple of 64 (128 with 8-bit logits); N overflows int32; bad exponent */
+  LMHEAD_E_SHAPE = -2,     /* P,G,T,d,V <= 0; ld < d; d not a multiple of one 128-byte K-step (64 for bf16, 32 for  */
+                           /* fp32, 128 with 8-bit logits); a size beyond the limits given at lmhead_desc; bad exponent */
   LMHEAD_E_DTYPE = -3,     /* dtype not LMHEAD_F32 / LMHEAD_BF16, or unknown flag bits  */
   LMHEAD_E_ALIGN = -4,     /* a matrix pointer is not 16-byte aligned, or ld*elem % 16  */
   LMHEAD_E_WORKSPACE = -5, /* ws_bytes smaller than lmhead_workspace_bytes()           */
@@ -72,14 +75,21 @@ enum {
                                     /* it changes the logits by up to ~6 % of their spread.             */
 };
 
-/* Problem descriptor (host memory). */
+/* Problem descriptor (host memory).
+ * Size limits: the matrix-core kernels consume K in steps of one 128-byte line per row, so d must be a
+ * multiple of 64 (bf16) or 32 (fp32) - the caller's W cannot be padded by the library, and a partial
+ * last step would read the next row's values.  Operand tiles are addressed with 32-bit byte offsets
+ * inside a 2 GiB window, which bounds every row pitch to 8 MiB: N + 320, V + 320 and ldH, ldW must each
+ * stay below 4 Mi elements for bf16 (2 Mi for fp32); LMHEAD_E_SHAPE otherwise.  Split larger batches
+ * by prompt (dW accumulates with LMHEAD_FLAG_ACCUM_DW). */
 typedef struct lmhead_desc {
   int32_t P, G, T;     /* R = P*G responses, N = R*T token slots                          */
-  int32_t d, V;        /* hidden size (multiple of 64) and vocabulary size                */
+  int32_t d, V;        /* hidden size (multiple of 64; 32 for fp32) and vocabulary size   */
   int32_t dtype;       /* LMHEAD_F32 or LMHEAD_BF16: storage type of H and W              */
   int32_t vocab_chunk; /* vocabulary chunk of the backward (columns of dZ held at once);  */
                        /* 0 = library default (as wide as ~48 GB of scratch allows, at    */
-                       /* most 32768).  Rounded up to a multiple of the 256-wide tile.    */
+                       /* most 262144, so small problems take the vocabulary in one       */
+                       /* chunk).  Rounded up to a multiple of the 256-wide tile.         */
   int32_t fp8_exp_h;   /* with LMHEAD_FLAG_FP8_LOGITS: H is scaled by 2^fp8_exp_h before rounding  */
                        /* (choose it so that max|H| * 2^e <= 448); otherwise must be 0            */
   int64_t ldH, ldW;    /* row strides of H and W in elements (>= d)                       */
@@ -94,6 +104,23 @@ LMHEAD_API size_t lmhead_workspace_bytes(const lmhead_desc* desc);
 /* Validates a descriptor on the host.  Returns LMHEAD_OK or the LMHEAD_E_* code that
  * the compute entry points would return for it. */
 LMHEAD_API int lmhead_validate_desc(const lmhead_desc* desc);
+
+/*
+ * Where a forward call leaves its integer indexing in the workspace (host-only query; for tests and
+ * diagnostics - the benchmark's problem statement asks for these integers to be checked bit for bit).
+ * Valid after lmhead_logprob_fwd / _fwd_multi on `ws` until `ws` is passed to another call.
+ *   LMHEAD_WS_NV           int32        N_v = number of valid slots
+ *   LMHEAD_WS_ROW_SLOT     int32[Ncap]  compaction map: entry k < N_v is the slot of the k-th valid token
+ *                                       (slot order); -1 from N_v up to the next multiple of 256
+ *   LMHEAD_WS_TOK_C        int32[Ncap]  tok[row_slot[k]] (-1 for an id outside [0, V) and on the padding)
+ *   LMHEAD_WS_GATHERED_ID  int32[npol][Ncap]  vocabulary column whose logit the logits kernel captured
+ *                                       as the target logit of compact row k (-1: none captured)
+ * Ncap = N rounded up to a multiple of 256.  npol = 1 for lmhead_logprob_fwd.
+ * *offset = byte offset of the region from `ws`, *bytes = its size.
+ */
+enum { LMHEAD_WS_NV = 0, LMHEAD_WS_ROW_SLOT = 1, LMHEAD_WS_TOK_C = 2, LMHEAD_WS_GATHERED_ID = 3 };
+LMHEAD_API int lmhead_workspace_region(const lmhead_desc* desc, int32_t npol, int32_t which,
+                                       size_t* offset, size_t* bytes);
 
 /*
  * Forward (the log-softmax inside L_CE, Eq. 9).  For every valid slot i:
@@ -221,8 +248,9 @@ LMHEAD_API int flowrl_tb_loss(const float* logp, const float* logp_ref, const fl
 LMHEAD_API int lmhead_check(void* ws, void* stream);
 
 /*
- * Optional instrumentation for benchmarks (the only process-wide state of the library; not
- * thread-safe).  lmhead_timing_enable(1) makes lmhead_logprob_fwd/bwd and the dynakv_* calls
+ * Optional instrumentation for benchmarks.  This is the only process-wide mutable state of the
+ * library and it is NOT thread-safe: enable, run and read from one thread, with no other thread
+ * inside a library call meanwhile.  lmhead_timing_enable(1) makes lmhead_logprob_fwd/bwd and the dynakv_* calls
  * (dynakv.h) bracket each of their main kernel launches with two HIP events on the launch stream (a fixed pool of 8192
  * pairs; launches beyond it are not timed) and clears earlier records; (0) turns it off.
  * lmhead_timing_read waits for the recorded events and returns, for one kernel kind

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "lmhead_multi_workspace_bytes", "lmhead_logprob_fwd_multi",
     "group_advantage",
     "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "ce_loss", "lmhead_check",
-    "lmhead_timing_enable", "lmhead_timing_read",
+    "lmhead_timing_enable", "lmhead_timing_read", "lmhead_workspace_region",
 ]
 
 ERRORS = {
@@ -95,6 +95,8 @@ def load_library():
     lib.ce_loss.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.lmhead_check.restype = C.c_int
     lib.lmhead_check.argtypes = [vp, vp]
+    lib.lmhead_workspace_region.restype = C.c_int
+    lib.lmhead_workspace_region.argtypes = [dp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
     lib.lmhead_timing_enable.restype = C.c_int
     lib.lmhead_timing_enable.argtypes = [C.c_int]
     lib.lmhead_timing_read.restype = C.c_int
@@ -121,6 +123,17 @@ def loss_workspace_bytes(P: int, G: int, T: int) -> int:
 
 def validate_desc(desc: LmheadDesc) -> int:
     return int(load_library().lmhead_validate_desc(C.byref(desc)))
+
+
+WS_NV, WS_ROW_SLOT, WS_TOK_C, WS_GATHERED_ID = 0, 1, 2, 3
+
+
+def workspace_region(desc: LmheadDesc, npol: int, which: int):
+    """(byte offset, bytes) of one of the integer index regions a forward call leaves in its workspace."""
+    off, nbytes = C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().lmhead_workspace_region(C.byref(desc), npol, which, C.byref(off), C.byref(nbytes)),
+           "lmhead_workspace_region")
+    return off.value, nbytes.value
 
 
 def _ptr(t) -> Optional[int]:

@@ -50,7 +50,7 @@ struct WsLayout {
   int ksplit;       // dH: slices of the contraction per output tile (> 1 only when the tile grid
                     // alone would leave most of the chip idle); partial tiles go to dHpart
   size_t dHpart;
-  size_t hdr, cu_len, row_slot, tok_c, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, Hc8, W8, total;
+  size_t hdr, cu_len, row_slot, tok_c, gid, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, Hc8, W8, total;
 };
 
 // Default backward chunk: as wide as keeps the two dZ copies (worst case: every slot valid)
@@ -97,6 +97,7 @@ static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
   L.cu_len = take((size_t)(L.R + 1) * 4);
   L.row_slot = take((size_t)L.Ncap * 4);
   L.tok_c = take((size_t)L.Ncap * 4);
+  L.gid = take((size_t)npol * L.Ncap * 4);
   L.g_c = take((size_t)L.Ncap * 4);
   L.lse_c = take((size_t)L.Ncap * 4);
   L.zy = take((size_t)npol * L.Ncap * 4);
@@ -139,11 +140,12 @@ hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t
                         int32_t* row_slot, uint8_t* mask_out, int32_t* cu_out, hipStream_t s);
 
 // Gathers the valid rows of H into the dense, zero-padded Hc[Ncap x d]; also compacts tok
-// (range-checked), and optionally g_logp and lse.  The npol vectors zy[p * Ncap + .] are cleared.
+// (range-checked), and optionally g_logp and lse.  The npol vectors zy[p * Ncap + .] are cleared and
+// the npol vectors gid[p * Ncap + .] set to -1.
 hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
                           const float* g, const float* lse, int64_t N, WsHeader* hdr,
                           const int32_t* row_slot, void* Hc, int64_t ldHc, int32_t* tok_c, float* g_c,
-                          float* lse_c, float* zy, int npol, int64_t Ncap, hipStream_t s);
+                          float* lse_c, float* zy, int32_t* gid, int npol, int64_t Ncap, hipStream_t s);
 
 // out[c][r] = in[r][c] for r < rows (rows read from the header when rows_from_nv), zero padding
 // up to out's extent [cols_p x rows_p] (pitch ld_out >= rows_p).
@@ -164,6 +166,7 @@ struct FwdArgs {
   const WsHeader* hdr;
   float* part;         // [npol][3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
   float* zy;           // [npol][Ncap]
+  int32_t* gid;        // [npol][Ncap]: vocabulary column whose logit was captured as the target's
   float zscale;        // logits = accumulator * zscale (1, or 2^-(e_H + e_W) for e4m3 operands)
 };
 hipError_t launch_fwd(int dtype, const FwdArgs& a, hipStream_t s);

@@ -16,7 +16,8 @@ int validate(const lmhead_desc* d) {
   if (d->dtype != LMHEAD_F32 && d->dtype != LMHEAD_BF16) return LMHEAD_E_DTYPE;
   if (d->flags & ~(uint32_t)(LMHEAD_FLAG_ACCUM_DW | LMHEAD_FLAG_FP8_LOGITS | LMHEAD_FLAG_DH_BF16)) return LMHEAD_E_DTYPE;
   if (d->vocab_chunk < 0) return LMHEAD_E_SHAPE;
-  if (d->d % 64 != 0) return LMHEAD_E_SHAPE;
+  // one K-step of the matrix-core loops is a 128-byte line of a row: 64 bf16 or 32 fp32 values
+  if (d->d % (d->dtype == LMHEAD_BF16 ? 64 : 32) != 0) return LMHEAD_E_SHAPE;
   if (d->flags & LMHEAD_FLAG_FP8_LOGITS) {
     // one K-step of the 8-bit kernels is 128 values; exponents beyond +-60 cannot be meant
     if (d->d % 128 != 0 || d->fp8_exp_h < -60 || d->fp8_exp_h > 60 || d->fp8_exp_w < -60 || d->fp8_exp_w > 60)
@@ -31,6 +32,19 @@ int validate(const lmhead_desc* d) {
   if ((int64_t)d->V > (int64_t)INT32_MAX - 2 * kTile) return LMHEAD_E_SHAPE;
   const int esz = d->dtype == LMHEAD_BF16 ? 2 : 4;
   if ((d->ldH * esz) % 16 != 0 || (d->ldW * esz) % 16 != 0) return LMHEAD_E_ALIGN;
+  // The matrix-core kernels address an operand tile through one buffer descriptor with 32-bit byte
+  // offsets inside a 2 GiB window: the last row of a 256-row tile plus the contraction's extent must
+  // stay below 2^31.  The widest rows are the token-major operand copies of the backward (N slots wide).
+  {
+    const WsLayout L = make_layout(d, kMaxPolicies);
+    int64_t pitch = d->ldW;
+    for (int64_t p : {L.ldHc, L.ldHcT, L.ldWT, L.ldZ, L.ldZT}) pitch = p > pitch ? p : pitch;
+    if ((int64_t)kTile * pitch * esz >= (1ll << 31)) return LMHEAD_E_SHAPE;
+    // 1-D launch grids (tiles of the largest kernel, rounded up by the tile walk) must fit HIP's limit
+    const int64_t tok_tiles = L.Ncap / kTile + 8 * 16, voc_tiles = L.Vp / kTile, d_tiles = L.dp / kTile;
+    const int64_t widest = voc_tiles * kMaxPolicies > d_tiles * 8 ? voc_tiles * kMaxPolicies : d_tiles * 8;
+    if (widest * tok_tiles > INT32_MAX || d_tiles * (voc_tiles + 8 * 16) > INT32_MAX) return LMHEAD_E_SHAPE;
+  }
   return LMHEAD_OK;
 }
 
@@ -71,6 +85,21 @@ size_t lmhead_workspace_bytes(const lmhead_desc* desc) {
   return make_layout(desc).total;
 }
 
+int lmhead_workspace_region(const lmhead_desc* desc, int32_t npol, int32_t which, size_t* offset, size_t* bytes) {
+  const int rc = validate(desc);
+  if (rc != LMHEAD_OK) return rc;
+  if (npol < 1 || npol > kMaxPolicies || which < 0 || which > LMHEAD_WS_GATHERED_ID) return LMHEAD_E_SHAPE;
+  if (!offset || !bytes) return LMHEAD_E_NULL;
+  const WsLayout L = make_layout(desc, npol);
+  switch (which) {
+    case LMHEAD_WS_NV: *offset = L.hdr + offsetof(WsHeader, nv); *bytes = 4; break;
+    case LMHEAD_WS_ROW_SLOT: *offset = L.row_slot; *bytes = (size_t)L.Ncap * 4; break;
+    case LMHEAD_WS_TOK_C: *offset = L.tok_c; *bytes = (size_t)L.Ncap * 4; break;
+    default: *offset = L.gid; *bytes = (size_t)npol * L.Ncap * 4; break;
+  }
+  return LMHEAD_OK;
+}
+
 // Shared body of the two forward entry points: index, compaction, one logits launch over all
 // npol weight matrices, then one merge of the per-tile statistics per matrix.
 static int forward(const lmhead_desc* desc, const void* H, const void* const* W, int npol, const int32_t* tok,
@@ -86,7 +115,7 @@ static int forward(const lmhead_desc* desc, const void* H, const void* const* W,
                       mask, cu_len, s));
   LM_TRY(launch_compact(desc->dtype, H, desc->ldH, desc->d, desc->V, tok, nullptr, nullptr, L.N, hdr,
                         w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c), nullptr,
-                        nullptr, w.at<float>(L.zy), npol, L.Ncap, s));
+                        nullptr, w.at<float>(L.zy), w.at<int32_t>(L.gid), npol, L.Ncap, s));
   const bool fp8 = (desc->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
   FwdArgs fa{};
   fa.zscale = 1.0f;
@@ -120,6 +149,7 @@ static int forward(const lmhead_desc* desc, const void* H, const void* const* W,
   fa.hdr = hdr;
   fa.part = w.at<float>(L.part);
   fa.zy = w.at<float>(L.zy);
+  fa.gid = w.at<int32_t>(L.gid);
   {
     TimedLaunch tl(0, s);
     LM_TRY(launch_fwd(fp8 ? kDtypeFp8 : desc->dtype, fa, s));
@@ -184,7 +214,7 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
                       nullptr, nullptr, s));
   LM_TRY(launch_compact(dt, H, desc->ldH, desc->d, desc->V, tok, g_logp, lse, L.N, hdr,
                         w.at<int32_t>(L.row_slot), w.at<void>(L.Hc), L.ldHc, w.at<int32_t>(L.tok_c),
-                        w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), 1, L.Ncap, s));
+                        w.at<float>(L.g_c), w.at<float>(L.lse_c), w.at<float>(L.zy), w.at<int32_t>(L.gid), 1, L.Ncap, s));
   // K-contiguous copies of the two operands that the backward contracts along their rows
   LM_TRY(launch_transpose(dt, w.at<void>(L.Hc), L.ldHc, L.Ncap, desc->d, true, hdr, w.at<void>(L.HcT),
                           L.ldHcT, L.Ncap, L.dp, s));

@@ -102,7 +102,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H
                                                       const int32_t* __restrict__ row_slot,
                                                       char* __restrict__ Hc, int32_t* __restrict__ tok_c,
                                                       float* __restrict__ g_c, float* __restrict__ lse_c,
-                                                      float* __restrict__ zy, int npol, int64_t Ncap) {
+                                                      float* __restrict__ zy, int32_t* __restrict__ gid,
+                                                      int npol, int64_t Ncap) {
   const int nv = hdr->nv;
   const int64_t nvp = ((int64_t)nv + kTile - 1) / kTile * kTile;
   const int64_t k = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -124,7 +125,10 @@ __global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H
       tok_c[k] = tk;
       if (g_c) g_c[k] = g[slot];
       if (lse_c) lse_c[k] = lse[slot];
-      for (int p = 0; p < npol; ++p) zy[p * Ncap + k] = 0.f;
+      for (int p = 0; p < npol; ++p) {
+        zy[p * Ncap + k] = 0.f;
+        gid[p * Ncap + k] = -1;
+      }
     }
   } else {
     const u4 z = {0, 0, 0, 0};
@@ -133,7 +137,10 @@ __global__ __launch_bounds__(256) void compact_kernel(const char* __restrict__ H
       tok_c[k] = -1;
       if (g_c) g_c[k] = 0.f;
       if (lse_c) lse_c[k] = 0.f;
-      for (int p = 0; p < npol; ++p) zy[p * Ncap + k] = 0.f;
+      for (int p = 0; p < npol; ++p) {
+        zy[p * Ncap + k] = 0.f;
+        gid[p * Ncap + k] = -1;
+      }
     }
   }
 }
@@ -318,12 +325,12 @@ hipError_t launch_index(const int32_t* len, int R, int T, WsHeader* hdr, int32_t
 hipError_t launch_compact(int dtype, const void* H, int64_t ldH, int d, int V, const int32_t* tok,
                           const float* g, const float* lse, int64_t N, WsHeader* hdr,
                           const int32_t* row_slot, void* Hc, int64_t ldHc, int32_t* tok_c, float* g_c,
-                          float* lse_c, float* zy, int npol, int64_t Ncap, hipStream_t s) {
+                          float* lse_c, float* zy, int32_t* gid, int npol, int64_t Ncap, hipStream_t s) {
   const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
   const int64_t cap = (N + kTile - 1) / kTile * kTile;
   hipLaunchKernelGGL(compact_kernel, dim3((unsigned)(cap / 4)), dim3(256), 0, s,
                      static_cast<const char*>(H), ldH * esz, d * esz, ldHc * esz, V, tok, g, lse, hdr, row_slot,
-                     static_cast<char*>(Hc), tok_c, g ? g_c : nullptr, lse ? lse_c : nullptr, zy, npol, Ncap);
+                     static_cast<char*>(Hc), tok_c, g ? g_c : nullptr, lse ? lse_c : nullptr, zy, gid, npol, Ncap);
   return hipGetLastError();
 }
 

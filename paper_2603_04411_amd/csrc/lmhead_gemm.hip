@@ -6,10 +6,12 @@
 // fwd_kernel and dz_kernel also exist for 8-bit (e4m3) copies of their operands.
 //
 // Orientation: the vocabulary (or d) runs along the MFMA M axis and tokens (or vocabulary
-// rows of dW) along N.  With the 32x32 accumulator layout a lane then owns ONE token column
-// and 16*TM vocabulary entries of it, so the softmax statistics are reduced inside the lane
-// and need a single cross-lane step per tile; and a lane's four consecutive M entries are
-// contiguous in the row-major outputs (dZ row, dH row, dW row).
+// rows of dW) along N.  With the MFMA accumulator layouts (16x16 blocks for bf16, 32x32 for fp32
+// and e4m3) a lane then owns ONE token column per block and 4 (or 16) vocabulary entries of it, so
+// the softmax statistics are reduced inside the lane and need two (or one) cross-lane steps per
+// tile; and a lane's four consecutive M entries are contiguous in the row-major outputs (dZ row,
+// dH row, dW row).
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 #pragma unroll
   for (int p = 1; p < kMaxPolicies; ++p) Wp = (pol == p) ? static_cast<const char*>(a.W[p]) : Wp;
   float* const zy = a.zy + (size_t)pol * a.Ncap;
+  int32_t* const gid = a.gid + (size_t)pol * a.Ncap;
   float* const part = a.part + (size_t)pol * 3 * a.ntiles * a.Ncap;
   const int64_t n0 = (int64_t)nb * G::BN;
   const int m0 = tile * G::BM;
@@ -126,7 +129,11 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
             zsel = eq ? acc[i][j][v] : zsel;
             found |= eq;
           }
-        if (found) zy[n0 + G::n_of(j)] = zsel * a.zscale;
+        if (found) {
+          zy[n0 + G::n_of(j)] = zsel * a.zscale;
+          // vocabulary column of the accumulator element just selected (the compare above held for it)
+          gid[n0 + G::n_of(j)] = m0 + G::m_base() + relj[j];
+        }
       }
     }
   }
@@ -497,10 +504,19 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   }
 }
 
-template <typename K>
-hipError_t allow_lds(K kernel, int bytes) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+// Raises the kernel's dynamic LDS limit to `bytes`; asked of the runtime once per kernel and device
+// (the kernel is a template argument so that each one keeps its own record).
+template <auto kernel>
+hipError_t allow_lds(int bytes) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<bool> done[kMaxDev];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < kMaxDev && done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < kMaxDev) done[dev].store(true, std::memory_order_release);
+  return e;
 }
 
 }  // namespace
@@ -509,7 +525,7 @@ template <typename E>
 static hipError_t launch_fwd_e(const FwdArgs& a, hipStream_t s) {
   using G = Tile<E>;
   const dim3 grid(xcd_grid_size(a.ntiles * a.npol, a.Ncap / kTile, kFwdMapBy));
-  hipError_t e = allow_lds(fwd_kernel<E>, G::LDS_BYTES);
+  hipError_t e = allow_lds<fwd_kernel<E>>(G::LDS_BYTES);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fwd_kernel<E>, grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();
@@ -524,7 +540,7 @@ template <typename E, typename EO>
 static hipError_t launch_dz_e(const DzArgs& a, hipStream_t s) {
   using G = Tile<E>;
   const dim3 grid(xcd_grid_size(a.ntiles, a.Ncap / kTile, kMapBy));
-  hipError_t e = allow_lds(dz_kernel<E, EO>, G::LDS_BYTES);
+  hipError_t e = allow_lds<dz_kernel<E, EO>>(G::LDS_BYTES);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((dz_kernel<E, EO>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();
@@ -540,7 +556,7 @@ template <typename E, int Role>
 static hipError_t launch_gemm_t_impl(const GemmTArgs& a, hipStream_t s) {
   using G = Tile<E>;
   const dim3 grid(xcd_grid_size((a.M + kTile - 1) / kTile, a.n_tiles_cap * a.ksplit, kMapBy));
-  hipError_t e = allow_lds(gemm_t_kernel<E, Role>, G::LDS_BYTES);
+  hipError_t e = allow_lds<gemm_t_kernel<E, Role>>(G::LDS_BYTES);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_t_kernel<E, Role>), grid, dim3(G::NT), G::LDS_BYTES, s, a);
   return hipGetLastError();

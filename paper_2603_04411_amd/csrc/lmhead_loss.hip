@@ -23,6 +23,15 @@ __device__ inline float block_sum_256(float x, float* sh /*[4]*/) {
   return (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
+__device__ inline int block_sum_256_int(int x, int* sh /*[4]*/) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
 // One wavefront per prompt.
 __global__ __launch_bounds__(64) void advantage_kernel(const float* __restrict__ reward, int G, float eps,
                                                        int ddof, float* __restrict__ adv) {
@@ -112,19 +121,22 @@ __global__ __launch_bounds__(256) void grpo_final_kernel(const float* __restrict
                                                          const int32_t* __restrict__ len, int R, int T,
                                                          float* __restrict__ loss, float* __restrict__ stats) {
   __shared__ float sh[4];
+  __shared__ int shi[4];
   float a[4] = {0.f, 0.f, 0.f, 0.f};
   for (int q = threadIdx.x; q < nparts; q += 256)
 #pragma unroll
     for (int c = 0; c < 4; ++c) a[c] += ws[(size_t)q * 4 + c];
-  float nvf = 0.f;
-  for (int q = threadIdx.x; q < R; q += 256) nvf += (float)min(max(len[q], 0), T);
+  // N_v is counted in integers (exact for any N) and converted once
+  int nvi = 0;
+  for (int q = threadIdx.x; q < R; q += 256) nvi += min(max(len[q], 0), T);
 #pragma unroll
   for (int c = 0; c < 4; ++c) a[c] = block_sum_256(a[c], sh);
-  nvf = block_sum_256(nvf, sh);
+  const int nv = block_sum_256_int(nvi, shi);
   if (threadIdx.x == 0) {
     loss[0] = a[0];
     if (stats) {
-      const float inv = nvf > 0.f ? 1.f / nvf : 0.f;
+      const float nvf = (float)nv;
+      const float inv = nv > 0 ? 1.f / nvf : 0.f;
       stats[0] = a[1] * inv;
       stats[1] = a[2] * inv;
       stats[2] = a[3] * inv;
@@ -166,12 +178,14 @@ __global__ __launch_bounds__(256) void ce_final_kernel(const float* __restrict__
                                                        const int32_t* __restrict__ len, int R, int T,
                                                        float* __restrict__ loss) {
   __shared__ float sh[4];
-  float a = 0.f, nvf = 0.f;
+  __shared__ int shi[4];
+  float a = 0.f;
+  int nvi = 0;
   for (int q = threadIdx.x; q < nparts; q += 256) a += ws[q];
-  for (int q = threadIdx.x; q < R; q += 256) nvf += (float)min(max(len[q], 0), T);
+  for (int q = threadIdx.x; q < R; q += 256) nvi += min(max(len[q], 0), T);
   a = block_sum_256(a, sh);
-  nvf = block_sum_256(nvf, sh);
-  if (threadIdx.x == 0) loss[0] = nvf > 0.f ? -a / nvf : 0.f;
+  const int nv = block_sum_256_int(nvi, shi);
+  if (threadIdx.x == 0) loss[0] = nv > 0 ? -a / (float)nv : 0.f;
 }
 
 // Trajectory balance, pass 1: per (response, block) sums of logp and logp_ref over valid slots.

@@ -17,16 +17,16 @@ def to_device(a: np.ndarray):
 class GpuProblem:
     """Device-resident tensors of one workload plus its workspace."""
 
-    def __init__(self, cfg, H, W, tok, lens, vocab_chunk=0, flags=0, fp8_exp_h=0, fp8_exp_w=0):
+    def __init__(self, cfg, H, W, tok, lens, vocab_chunk=0, flags=0, fp8_exp_h=0, fp8_exp_w=0, ldH=None, ldW=None):
         import torch
         import paper_2603_04411_amd as L
         self.L = L
         self.cfg = cfg
         self.desc = L.make_desc(cfg.P, cfg.G, cfg.T, cfg.d, cfg.V, cfg.dtype, vocab_chunk=vocab_chunk, flags=flags,
-                                fp8_exp_h=fp8_exp_h, fp8_exp_w=fp8_exp_w)
+                                fp8_exp_h=fp8_exp_h, fp8_exp_w=fp8_exp_w, ldH=ldH, ldW=ldW)
         assert L.validate_desc(self.desc) == 0
-        self.H = to_device(H)
-        self.W = to_device(W)
+        self.H = to_device(widen_rows(H, ldH))
+        self.W = to_device(widen_rows(W, ldW))
         self.tok = to_device(np.ascontiguousarray(tok, dtype=np.int32))
         self.lens = to_device(np.ascontiguousarray(lens, dtype=np.int32))
         self.ws = torch.empty(L.workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
@@ -55,6 +55,7 @@ class GpuProblem:
         lse = torch.full((cfg.N,), 7.0, **f)
         ent = torch.full((cfg.N,), 7.0, **f) if want_entropy else None
         ws = torch.empty(self.L.multi_workspace_bytes(self.desc, len(Ws)), dtype=torch.uint8, device="cuda")
+        self.ws_multi = ws
         self.L.lmhead_logprob_fwd_multi(self.desc, self.H, Ws, self.tok, self.lens, logps, lse, ent, None, None, ws)
         assert self.L.lmhead_check(ws) == 0
         return logps, lse, ent
@@ -106,8 +107,47 @@ class GpuProblem:
         self.L.ce_loss(logp, self.lens, cfg.R, cfg.T, loss, g, self.loss_ws)
         return loss, g
 
+    def index_regions(self, ws=None, npol=1):
+        """(N_v, row_slot[Ncap], tok_c[Ncap], gathered_id[npol][Ncap]) as the last forward left them in `ws`."""
+        import torch
+        ws = self.ws if ws is None else ws
+        torch.cuda.synchronize()
+        out = []
+        for which in (self.L.WS_NV, self.L.WS_ROW_SLOT, self.L.WS_TOK_C, self.L.WS_GATHERED_ID):
+            off, nbytes = self.L.workspace_region(self.desc, npol, which)
+            out.append(ws[off:off + nbytes].cpu().numpy().view(np.int32).copy())
+        ncap = out[1].size
+        return int(out[0][0]), out[1], out[2], out[3].reshape(npol, ncap)
+
     def check(self):
         return self.L.lmhead_check(self.ws)
+
+
+def widen_rows(a: np.ndarray, ld):
+    """Rows of `a` embedded in a buffer with row stride `ld` elements; the gap holds a non-zero filler
+    (bf16 / fp32 2.0) so that a kernel that ignored the stride would not pass by reading zeros."""
+    if ld is None or ld == a.shape[1]:
+        return a
+    fill = 0x4000 if a.dtype == np.uint16 else 2.0
+    wide = np.full((a.shape[0], ld), fill, dtype=a.dtype)
+    wide[:, : a.shape[1]] = a
+    return wide
+
+
+def assert_index_parity(gp, o_row_slot, tok, ws=None, npol=1):
+    """Bit-exact check of the compaction map, the compacted token ids and the gathered vocabulary columns
+    against the oracle's index_build (integers: ==)."""
+    nv, row_slot, tok_c, gid = gp.index_regions(ws, npol)
+    assert nv == o_row_slot.size
+    assert np.array_equal(row_slot[:nv], o_row_slot), "compaction map"
+    pad_end = (nv + 255) // 256 * 256
+    assert np.all(row_slot[nv:pad_end] == -1), "compaction map is padded with -1 up to the tile multiple"
+    want = np.asarray(tok, dtype=np.int32)[o_row_slot]
+    assert np.array_equal(tok_c[:nv], want), "compacted token ids"
+    assert np.all(tok_c[nv:pad_end] == -1)
+    for p in range(npol):
+        assert np.array_equal(gid[p, :nv], want), "gathered vocabulary column != sampled token id"
+        assert np.all(gid[p, nv:pad_end] == -1)
 
 
 def np64(t):

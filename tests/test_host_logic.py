@@ -63,9 +63,54 @@ def test_descriptor_validation_codes(lib):
         assert L.validate_desc(desc) == code, (change, L.validate_desc(desc))
         assert L.workspace_bytes(desc) == 0
     assert lib.lmhead_validate_desc(None) == -1
+    # one K-step is a 128-byte line: 32 fp32 or 64 bf16 values
+    assert L.validate_desc(L.make_desc(2, 4, 32, 96, 4096, "f32")) == 0
+    assert L.validate_desc(L.make_desc(2, 4, 32, 48, 4096, "f32")) == -2
+    assert L.validate_desc(L.make_desc(2, 4, 32, 96, 4096, "bf16")) == -2
     fp8 = L.make_desc(2, 4, 32, 256, 4096, "bf16", flags=4, fp8_exp_h=6, fp8_exp_w=12)
     plain = L.make_desc(2, 4, 32, 256, 4096, "bf16")
     assert L.validate_desc(fp8) == 0 and L.workspace_bytes(fp8) > L.workspace_bytes(plain)
+
+
+def test_sizes_beyond_the_32_bit_tile_offsets_are_rejected(lib):
+    # A 256-row operand tile is addressed with 32-bit byte offsets in a 2 GiB window, so every row pitch
+    # must stay below 2^31 / 256 bytes; the widest rows are N (+ padding) or V (+ padding) elements.
+    def code(P, T, V, dtype, d=64, **kw):
+        return L.validate_desc(L.make_desc(P, 1, T, d, V, dtype, **kw))
+    assert code(16383, 256, 1000, "bf16") == 0            # N + 64 = 4194112 < 4 Mi elements of 2 bytes
+    assert code(16384, 256, 1000, "bf16") == -2           # N + 64 >= 4 Mi
+    assert code(8191, 256, 1000, "f32") == 0
+    assert code(8192, 256, 1000, "f32") == -2
+    assert code(2, 8, 16383 * 256, "bf16") == 0           # V + padding
+    assert code(2, 8, 16383 * 256 + 1, "bf16") == -2
+    assert code(2, 8, 1000, "bf16", ldW=1 << 22) == -2    # the caller's own row stride counts too
+    assert code(2, 8, 1000, "bf16", ldW=(1 << 22) - 8) == 0
+    assert L.workspace_bytes(L.make_desc(16384, 1, 256, 64, 1000, "bf16")) == 0
+    # the launch of a rejected size never happens: the compute entry points return the same code
+    p = 0x10000
+    bad = L.make_desc(16384, 1, 256, 64, 1000, "bf16")
+    assert lib.lmhead_logprob_bwd(C.byref(bad), p, p, p, p, p, p, p, p, p, 1 << 45, None) == -2
+
+
+def test_workspace_region_query(lib):
+    desc = L.make_desc(3, 4, 100, 128, 5000, "bf16")
+    total = L.workspace_bytes(desc)
+    ncap = (3 * 4 * 100 + 255) // 256 * 256
+    seen = []
+    for which, nbytes in ((L.WS_NV, 4), (L.WS_ROW_SLOT, 4 * ncap), (L.WS_TOK_C, 4 * ncap), (L.WS_GATHERED_ID, 4 * ncap)):
+        off, got = L.workspace_region(desc, 1, which)
+        assert got == nbytes and off % 4 == 0 and off + got <= total
+        seen.append((off, off + got))
+    seen.sort()
+    assert all(a[1] <= b[0] for a, b in zip(seen, seen[1:])), "regions do not overlap"
+    off3, bytes3 = L.workspace_region(desc, 3, L.WS_GATHERED_ID)
+    assert bytes3 == 3 * 4 * ncap and off3 + bytes3 <= L.multi_workspace_bytes(desc, 3)
+    o, b = C.c_size_t(), C.c_size_t()
+    q = lib.lmhead_workspace_region
+    assert q(C.byref(desc), 1, 9, C.byref(o), C.byref(b)) == -2
+    assert q(C.byref(desc), 0, 1, C.byref(o), C.byref(b)) == -2
+    assert q(C.byref(desc), 1, 1, None, C.byref(b)) == -1
+    assert q(C.byref(L.make_desc(3, 4, 100, 100, 5000, "bf16")), 1, 1, C.byref(o), C.byref(b)) == -2
 
 
 def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):

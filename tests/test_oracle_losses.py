@@ -163,6 +163,32 @@ def test_grpo_gradient_vs_autograd_and_fd():
         assert np.all(g[mask == 0] == 0)
 
 
+def test_grpo_abs_scale_bruteforce_python():
+    # sum_i w_i |l_i| term by term, both aggregation modes, with and without the KL term; a scale off by
+    # a constant factor (which would loosen every near-zero loss tolerance) fails here
+    lp, lo, lr, adv, lens, P, G, T = _grpo_case(7, spread=1.0)
+    R, nv = P * G, int(lens.sum())
+    for agg in (0, 1):
+        for ref in (lr, None):
+            tot = 0.0
+            for r in range(R):
+                for t in range(int(lens[r])):
+                    i = r * T + t
+                    rho = math.exp(lp[i] - lo[i])
+                    s = min(rho * adv[r], min(max(rho, 0.75), 1.25) * adv[r])
+                    k3 = 0.0
+                    if ref is not None:
+                        dl = ref[i] - lp[i]
+                        k3 = math.exp(dl) - dl - 1
+                    w = 1 / (R * lens[r]) if agg == 0 else 1 / nv
+                    tot += w * abs(-s + 0.07 * k3)
+            got = O.grpo_abs_scale(lp, lo, ref, adv, lens, P, G, T, 0.25, 0.25, 0.07, agg)
+            assert abs(got - tot) < 1e-12 * max(1.0, tot)
+    # single token, hand value: A = 2, rho = 1, no KL: |l| = 2, w = 1
+    one = O.grpo_abs_scale(np.array([-1.0]), np.array([-1.0]), None, np.array([2.0]), np.array([1]), 1, 1, 1)
+    assert one == 2.0
+
+
 def test_grpo_abs_scale_bounds_loss():
     lp, lo, lr, adv, lens, P, G, T = _grpo_case(6)
     loss, _, _ = O.grpo_loss(lp, lo, lr, adv, lens, P, G, T)
