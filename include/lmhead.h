@@ -214,6 +214,24 @@ LMHEAD_API int grpo_loss(const float* logp, const float* logp_old, const float* 
               void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * grpo_loss for callers that cannot allocate or carry a workspace: code under HIP graph capture, tight
+ * serving / training loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * grpo_loss (bit-identical outputs: the same kernels run), without `ws`: the block partials live in a
+ * 1 MiB device array that is part of the library image (one copy per GPU the library runs on, held until
+ * the process ends).  The call allocates and frees nothing.
+ *   Limit: P * G * ceil(T / 2048) <= 65536 blocks; beyond it LMHEAD_E_WORKSPACE, before any launch.
+ *   The array's device address is looked up on the first call on each device (a symbol lookup, no
+ *   allocation); make that first call outside graph capture.
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ *   streams or threads) race; calls on one stream are ordered and safe.  Nothing needs clearing between
+ *   calls: each call writes every partial it later reads.
+ */
+LMHEAD_API int grpo_loss_noalloc(const float* logp, const float* logp_old, const float* logp_ref,
+              const float* adv, const int32_t* len, int32_t P, int32_t G, int32_t T,
+              float clip_lo, float clip_hi, float kl_coef, int32_t agg_mode,
+              float* loss, float* g_logp, float* stats, void* stream);
+
+/*
  * Cross-entropy over the target tokens: the L_CE term of the paper's training objective
  * L = L_CE + alpha R^2 (Sec. 3.3, Eq. 9), evaluated from the forward's log-probabilities:
  *     loss = -(1/N_v) sum_{valid i} logp_i,      g_logp_i = -1/N_v on valid slots, 0 on padding.

@@ -21,6 +21,7 @@ from .binding import (
     lmhead_logprob_bwd,
     group_advantage,
     grpo_loss,
+    grpo_loss_noalloc,
     flowrl_tb_loss,
     ce_loss,
     lmhead_check,
@@ -54,7 +55,7 @@ __all__ = [
     "dynakv_bwd_workspace_bytes", "dynakv_gate_bwd", "FLAG_LITERAL_FLIP", "FLAG_ACCUM_GRAD",
     "LmheadError", "LmheadDesc", "library_path", "load_library", "make_desc",
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
-    "lmhead_logprob_fwd", "lmhead_logprob_fwd_multi", "multi_workspace_bytes", "lmhead_logprob_bwd", "group_advantage", "grpo_loss",
+    "lmhead_logprob_fwd", "lmhead_logprob_fwd_multi", "multi_workspace_bytes", "lmhead_logprob_bwd", "group_advantage", "grpo_loss", "grpo_loss_noalloc",
     "flowrl_tb_loss", "ce_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
     "workspace_region", "WS_NV", "WS_ROW_SLOT", "WS_TOK_C", "WS_GATHERED_ID",
 ]

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "lmhead_abi_version", "lmhead_workspace_bytes", "lmhead_validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "lmhead_multi_workspace_bytes", "lmhead_logprob_fwd_multi",
     "group_advantage",
-    "lmhead_loss_workspace_bytes", "grpo_loss", "flowrl_tb_loss", "ce_loss", "lmhead_check",
+    "lmhead_loss_workspace_bytes", "grpo_loss", "grpo_loss_noalloc", "flowrl_tb_loss", "ce_loss", "lmhead_check",
     "lmhead_timing_enable", "lmhead_timing_read", "lmhead_workspace_region",
 ]
 
@@ -89,6 +89,8 @@ def load_library():
     lib.lmhead_loss_workspace_bytes.argtypes = [i32, i32, i32]
     lib.grpo_loss.restype = C.c_int
     lib.grpo_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, f32, f32, i32, vp, vp, vp, vp, sz, vp]
+    lib.grpo_loss_noalloc.restype = C.c_int
+    lib.grpo_loss_noalloc.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, f32, f32, i32, vp, vp, vp, vp]
     lib.flowrl_tb_loss.restype = C.c_int
     lib.flowrl_tb_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.ce_loss.restype = C.c_int
@@ -195,6 +197,14 @@ def grpo_loss(logp, logp_old, logp_ref, adv, lens, P, G, T, clip_lo, clip_hi, kl
         _ptr(logp), _ptr(logp_old), _ptr(logp_ref), _ptr(adv), _ptr(lens), P, G, T, clip_lo, clip_hi, kl_coef,
         agg_mode, _ptr(loss), _ptr(g_logp), _ptr(stats), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "grpo_loss")
+
+
+def grpo_loss_noalloc(logp, logp_old, logp_ref, adv, lens, P, G, T, clip_lo, clip_hi, kl_coef, agg_mode,
+                      loss, g_logp, stats) -> None:
+    rc = load_library().grpo_loss_noalloc(
+        _ptr(logp), _ptr(logp_old), _ptr(logp_ref), _ptr(adv), _ptr(lens), P, G, T, clip_lo, clip_hi, kl_coef,
+        agg_mode, _ptr(loss), _ptr(g_logp), _ptr(stats), _stream())
+    _check(rc, "grpo_loss_noalloc")
 
 
 def flowrl_tb_loss(logp, logp_ref, reward, logZ, lens, P, G, T, beta, loss, g_logp, g_logZ, resid, ws) -> None:

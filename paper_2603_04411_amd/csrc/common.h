@@ -257,6 +257,12 @@ hipError_t launch_flowrl(const float* lp, const float* lr, const float* reward, 
 
 constexpr int kLossSlotsPerBlock = 2048;
 
+// grpo_loss_noalloc keeps its block partials (four floats per block of kLossSlotsPerBlock slots of one
+// response) in a device array of the library image: at most this many blocks, 1 MiB.
+constexpr int kStaticLossParts = 65536;
+// Device address of that array on the current device (no allocation; resolved once per device).
+hipError_t static_scratch(float** out);
+
 // ---- optional per-kernel timing -------------------------------------------------------
 // When enabled, each MFMA kernel launch is bracketed by two HIP events recorded on the launch
 // stream.  The pool is fixed-size; launches beyond it are simply not timed.

@@ -350,6 +350,23 @@ int grpo_loss(const float* logp, const float* logp_old, const float* logp_ref, c
   return LMHEAD_OK;
 }
 
+int grpo_loss_noalloc(const float* logp, const float* logp_old, const float* logp_ref, const float* adv,
+                      const int32_t* len, int32_t P, int32_t G, int32_t T, float clip_lo, float clip_hi,
+                      float kl_coef, int32_t agg_mode, float* loss, float* g_logp, float* stats, void* stream) {
+  const int rc = validate_pgt(P, G, T);
+  if (rc != LMHEAD_OK) return rc;
+  if (agg_mode != 0 && agg_mode != 1) return LMHEAD_E_SHAPE;
+  if (!logp || !logp_old || !adv || !len || !loss) return LMHEAD_E_NULL;
+  const int64_t nb = ((int64_t)T + kLossSlotsPerBlock - 1) / kLossSlotsPerBlock;
+  if ((int64_t)P * G * nb > kStaticLossParts) return LMHEAD_E_WORKSPACE;   // beyond the static scratch
+  float* scratch_dev = nullptr;
+  LM_TRY(static_scratch(&scratch_dev));
+  // every partial the final kernel reads is written by the first kernel of this call: nothing to clear
+  LM_TRY(launch_grpo(logp, logp_old, logp_ref, adv, len, P, G, T, clip_lo, clip_hi, kl_coef, agg_mode, loss,
+                     g_logp, stats, scratch_dev, static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
 int ce_loss(const float* logp, const int32_t* len, int32_t R, int32_t T, float* loss, float* g_logp,
             void* ws, size_t ws_bytes, void* stream) {
   const int rc = validate_pgt(R, 1, T);

@@ -2,7 +2,14 @@
 // importance-ratio surrogate with k3 KL, and the trajectory-balance residual.  All are O(N)
 // and HBM-bound: coalesced fp32 streams, wavefront shuffles for reductions, and fixed-order
 // two-level sums (per block, then one block over the partials) so results are reproducible.
+#include <atomic>
+
 #include "common.h"
+
+// Block partials of grpo_loss_noalloc: device memory that belongs to the library image instead of the
+// caller (each GPU the library runs on holds its own copy until the process ends).  Host code never
+// uses the array's name as an address: static_scratch() resolves the device address once per device.
+static __device__ __align__(256) float scratch[lmhead::kStaticLossParts * 4];
 
 namespace lmhead {
 
@@ -275,6 +282,28 @@ hipError_t launch_grpo(const float* lp, const float* lo, const float* lr, const 
                      1.f - clip_lo, 1.f + clip_hi, kl, agg, g, ws);
   hipLaunchKernelGGL(grpo_final_kernel, dim3(1), dim3(256), 0, s, ws, R * nb, len, R, T, loss, stats);
   return hipGetLastError();
+}
+
+// Device address of `scratch` on the current device (resolved on the first call per device, with that
+// device current; later calls read the kept pointer).
+hipError_t static_scratch(float** out) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<float*> ptr[kMaxDev];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+  float* p = ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!sym) return hipErrorInvalidSymbol;
+    p = static_cast<float*>(sym);
+    ptr[dev].store(p, std::memory_order_release);   // racing threads resolve the same address
+  }
+  *out = p;
+  return hipSuccess;
 }
 
 hipError_t launch_ce(const float* lp, const int32_t* len, int R, int T, float* loss, float* g, float* ws,
