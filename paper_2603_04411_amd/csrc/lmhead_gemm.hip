@@ -246,6 +246,138 @@ struct Store4<f32_tag> {
   __device__ static inline void one(void* p, float a) { *reinterpret_cast<float*>(p) = a; }
 };
 
+// Row order of the W tile in LDS for the 16x16-block dZ kernel.  LDS row R = 128 w + 16 i + r feeds
+// row r of MFMA block i of wave row w, and accumulator element v of lane group q belongs to block row
+// r = 4 q + v.  Loading vocabulary row 128 w + 32 (i / 2) + 8 q + 4 (i % 2) + v there makes the eight
+// values that a lane holds in blocks 2a and 2a + 1 the vocabulary rows 128 w + 32 a + 8 q + [0, 8) of its
+// token: 16 bytes of a dZ row, stored straight from registers.
+struct DzRows {
+  __device__ static constexpr int tile_row_of_lds_row(int R) {
+    return (R & ~127) + 32 * ((R >> 5) & 3) + 8 * ((R >> 2) & 3) + 4 * ((R >> 4) & 1) + (R & 3);
+  }
+  // compile-time part of the tile row of element v of block i (the rest depends on the lane only)
+  __device__ static constexpr int offset(int i, int v) { return 32 * (i >> 1) + 4 * (i & 1) + v; }
+};
+
+// Epilogue of the bf16 dZ kernel (16x16 blocks, permuted W rows): dZ = g (onehot - p) in bf16;
+//  - dZ [token][vocabulary] leaves straight from registers, 16 bytes per lane and block pair (a token's
+//    64 contiguous bytes come from the four lane groups of one store);
+//  - dZT [vocabulary][token] needs consecutive tokens, which sit in different lanes: the whole tile is
+//    staged once in LDS as [vocabulary row][token] and streamed out with 16 bytes per lane on
+//    line-contiguous rows.  One barrier per tile.
+// (Also tried: returning the packed block pairs transposed from the matrix cores, by multiplying them with a
+// 0/1 selection matrix, so that dZT leaves from registers too and LDS is not used at all.  It is exact, but
+// its stores, like those of dZ here, put consecutive lanes on different rows, and with both orientations
+// stored that way the kernel was 5 % slower than with this staging.)
+template <typename G>
+__device__ inline void dz_epilogue_direct(const DzArgs& a, typename G::Acc& acc, int m0, int mrel0, int64_t n0,
+                                          char* smem) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  constexpr int P2 = G::BN * 2 + 16;             // pitch of a staged [vocabulary row] of BN tokens
+  static_assert(G::BM * P2 <= G::LDS_BYTES && G::NB == 16 && G::VB == 4 && G::TM % 2 == 0, "staging fits in LDS");
+  const int q = G::lane() / 16, nl = G::lane() % 16;
+  const int mb = G::wave_m() * G::WM + 8 * q;    // lane part of the tile-relative vocabulary row
+  const int vlim = a.V - m0 - mb;                // vocabulary rows with offset >= vlim are padding
+  const float kz = kLog2e * a.zscale;            // logit = accumulator * zscale
+
+  // per-token scalars of this lane's token columns, requested in one batch (one exposed round trip per
+  // tile; requested before the main loop they do not fit next to its double-buffered fragments, and the
+  // compiler then spills each one right after its load, which serialises the loads)
+  float gj[G::TN], lsej[G::TN];
+  int relj[G::TN];
+  bool hit = false;
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const int64_t n = n0 + G::n_of(j);
+    gj[j] = a.g_c[n];
+    lsej[j] = a.lse_c[n];
+    relj[j] = a.tok_c[n];
+  }
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    hit |= (relj[j] >= m0) & (relj[j] < m0 + G::BM);
+    relj[j] -= m0 + mb;                          // compared with compile-time constants
+  }
+  // mode 0: no target of the wave's columns in this tile, no padding rows: dZ = -g p, with |g| folded into
+  //         the exponent and the sign applied to the packed pair.
+  // mode 1: a target somewhere in the tile: the one-hot term by a select (about a third of the tiles have
+  //         such a wave at V = 152 k).   mode 2: the vocabulary's last tile (padding rows give 0).
+  const int mode = (m0 + G::BM <= a.V) ? (__any(hit) ? 1 : 0) : 2;
+  char* const dZ = static_cast<char*>(a.dZ);
+  char* const dZT = static_cast<char*>(a.dZT);
+
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    const float g = gj[j];
+    const float bias = -lsej[j] * kLog2e;
+    const int rel = relj[j];
+    const int tl = G::n_of(j);                   // token within the tile
+    // rows 8 apart (the four lane groups) would share LDS banks: the 32-byte token groups of a staged
+    // row are permuted by (row / 8) % 4, which for this lane's rows is its lane group
+    char* const srow = smem + mb * P2 + (((tl >> 4) ^ q) << 5) + nl * 2;
+    char* const grow = dZ + ((size_t)(n0 + tl) * a.ldZ + mrel0 + mb) * 2;
+    auto emit = [&](auto mode_tag) {
+      constexpr int kMode = decltype(mode_tag)::value;
+      const float bias0 = bias + __builtin_amdgcn_logf(fabsf(g));   // log2 |g|; -inf for g = 0 gives p = 0
+      const uint32_t smask = g > 0.f ? 0x80008000u : 0u;
+      const float ng = -g;
+#pragma unroll
+      for (int ap = 0; ap < G::TM / 2; ++ap) {
+        u32x4_t pk;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float dz[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const int i = 2 * ap + (w >> 1), v = 2 * (w & 1) + u;
+            const float z = acc[i][j][v];
+            if constexpr (kMode == 0) {
+              dz[u] = fast_exp2(fmaf(z, kz, bias0));
+            } else {
+              const float p = fast_exp2(fmaf(z, kz, bias));
+              const bool oh = DzRows::offset(i, v) == rel;
+              if constexpr (kMode == 1)
+                dz[u] = fmaf(ng, p, oh ? g : 0.f);
+              else
+                dz[u] = (DzRows::offset(i, v) < vlim) ? g * ((oh ? 1.f : 0.f) - p) : 0.f;
+            }
+          }
+          const f32x2_t pair = {dz[0], dz[1]};
+          uint32_t word = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t));
+          if constexpr (kMode == 0) word ^= smask;
+          pk[w] = word;
+          const int mo = DzRows::offset(2 * ap + (w >> 1), 2 * (w & 1));
+          *reinterpret_cast<uint16_t*>(srow + mo * P2) = (uint16_t)word;
+          *reinterpret_cast<uint16_t*>(srow + (mo + 1) * P2) = (uint16_t)(word >> 16);
+        }
+        *reinterpret_cast<u32x4_t*>(grow + 64 * ap) = pk;
+        __builtin_amdgcn_sched_barrier(0);        // one block pair's values live at a time
+      }
+    };
+    if (mode == 0)
+      emit(std::integral_constant<int, 0>{});
+    else if (mode == 1)
+      emit(std::integral_constant<int, 1>{});
+    else
+      emit(std::integral_constant<int, 2>{});
+  }
+  lds_barrier();
+  // [vocabulary row][token] rows -> dZT
+  constexpr int CPR = G::BN * 2 / 16;            // 16-byte chunks per staged row
+  constexpr int RPP = G::NT / CPR;               // rows per pass
+  static_assert(RPP == 8, "the rows of a pass share their bank permutation");
+  const int c = threadIdx.x % CPR;
+  const int rin = threadIdx.x / CPR;
+#pragma unroll 8
+  for (int r0 = 0; r0 < G::BM; r0 += RPP) {
+    const int m = r0 + rin;
+    const int f = (r0 >> 3) & 3;
+    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(smem + m * P2 + ((((c >> 1) ^ f) << 5) | ((c & 1) << 4)));
+    *reinterpret_cast<u32x4_t*>(dZT + ((size_t)(mrel0 + m) * a.ldZT + n0 + c * 8) * 2) = v;
+  }
+}
+
 // E: type of the operands Hc and W (possibly e4m3 copies); EO: type of dZ / dZT.
 template <typename E, typename EO>
 __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
@@ -262,11 +394,16 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   const int64_t pitchH = a.ldHc * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
 
+  // With 16x16 blocks the rows of the W tile enter LDS in a permuted order (DzRows), chosen so that a
+  // lane's accumulators of two neighbouring blocks are EIGHT consecutive vocabulary entries of its token:
+  // 16 bytes of a dZ row, stored straight from registers.
+  constexpr bool kDirect = G::NB == 16;
   uint32_t offA[G::A_LD], offB[G::B_LD];
 #pragma unroll
   for (int q = 0; q < G::A_LD; ++q) {
     const int row = G::ldA_row(q);
-    offA[q] = (uint32_t)((min(m0 + row, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
+    const int vrow = kDirect ? DzRows::tile_row_of_lds_row(row) : row;
+    offA[q] = (uint32_t)((min(m0 + vrow, a.V - 1) - m0) * pitchW) + G::ld_byte(row);
   }
 #pragma unroll
   for (int q = 0; q < G::B_LD; ++q) {
@@ -274,24 +411,38 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
     offB[q] = (uint32_t)(row * pitchH) + G::ld_byte(row);
   }
 
-  // per-token scalars of this lane's token columns, fetched before the main loop (latency hidden)
-  float gj[G::TN], biasj[G::TN];
-  int relj[G::TN];
-  bool hit = false;
+  typename G::Acc acc;
+  G::zero(acc);
+  G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
+         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+  if constexpr (kDirect) {
+    static_assert(!kDirect || std::is_same<EO, bf16_tag>::value, "the 16x16 form is the bf16 kernel");
+    dz_epilogue_direct<G>(a, acc, m0, mrel0, n0, smem);
+    return;
+  }
+
+  // Per-token scalars of this lane's token columns, requested after the main loop in one batch (one
+  // exposed round trip per tile).  Requested before it they do not fit the register file next to the
+  // loop's double-buffered fragments: the compiler then spills each one right after its load, which
+  // serialises the loads (measured: a dozen dependent round trips per tile).
+  float gj[G::TN], lsej[G::TN];
+  int tkj[G::TN];
 #pragma unroll
   for (int j = 0; j < G::TN; ++j) {
     const int64_t n = n0 + G::n_of(j);
     gj[j] = a.g_c[n];
-    biasj[j] = -a.lse_c[n] * kLog2e;
-    const int tk = a.tok_c[n];
-    hit |= (tk >= m0) & (tk < m0 + G::BM);
-    relj[j] = tk - m0 - G::m_base();   // compared with compile-time constants
+    lsej[j] = a.lse_c[n];
+    tkj[j] = a.tok_c[n];
   }
-
-  typename G::Acc acc;
-  G::zero(acc);
-  G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
-                                  static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+  float biasj[G::TN];
+  int relj[G::TN];
+  bool hit = false;
+#pragma unroll
+  for (int j = 0; j < G::TN; ++j) {
+    biasj[j] = -lsej[j] * kLog2e;
+    hit |= (tkj[j] >= m0) & (tkj[j] < m0 + G::BM);
+    relj[j] = tkj[j] - m0 - G::m_base();   // compared with compile-time constants
+  }
 
   char* dZ = static_cast<char*>(a.dZ);
   char* dZT = static_cast<char*>(a.dZT);
