@@ -280,6 +280,20 @@ LMHEAD_API int lmhead_check(void* ws, void* stream);
 LMHEAD_API int lmhead_timing_enable(int on);
 LMHEAD_API int lmhead_timing_read(int kind, double* total_ms, int64_t* launches);
 
+/*
+ * Measurement aid (not part of the path): enqueues a bare loop of the matrix-core instruction behind the bf16
+ * contractions, v_mfma_f32_16x16x32_bf16, on operands that each thread loads once into registers:
+ * `workgroups` x 4 wavefronts, each doing `iters` x 64 MFMAs = iters x 2^20 flop, so the launch does
+ * workgroups * 4 * iters * 2^20 flop and moves no data meanwhile.  Timed by the caller (events on `stream`),
+ * it gives the rate the matrix cores sustain under the part's power management for the operand content
+ * given: the benchmark reports it for zeros and for random bf16 values next to the nominal peak.
+ *   operands  device, 256 bytes per thread (workgroups * 256 threads), any bf16 content        (in)
+ *   sink      device, one float per thread                                                     (out)
+ * LMHEAD_E_WORKSPACE if a buffer is smaller than that; LMHEAD_E_SHAPE for workgroups or iters <= 0.
+ */
+LMHEAD_API int lmhead_probe_mfma(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes,
+                                 int32_t workgroups, int32_t iters, void* stream);
+
 /* Version of this ABI (bumped on any incompatible change). */
 LMHEAD_API int lmhead_abi_version(void);
 

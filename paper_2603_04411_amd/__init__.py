@@ -27,6 +27,7 @@ from .binding import (
     lmhead_check,
     lmhead_timing_enable,
     lmhead_timing_read,
+    lmhead_probe_mfma,
     workspace_region,
     WS_NV, WS_ROW_SLOT, WS_TOK_C, WS_GATHERED_ID,
     EXPORTED_SYMBOLS,
@@ -57,5 +58,5 @@ __all__ = [
     "workspace_bytes", "loss_workspace_bytes", "validate_desc",
     "lmhead_logprob_fwd", "lmhead_logprob_fwd_multi", "multi_workspace_bytes", "lmhead_logprob_bwd", "group_advantage", "grpo_loss", "grpo_loss_noalloc",
     "flowrl_tb_loss", "ce_loss", "lmhead_check", "lmhead_timing_enable", "lmhead_timing_read", "EXPORTED_SYMBOLS",
-    "workspace_region", "WS_NV", "WS_ROW_SLOT", "WS_TOK_C", "WS_GATHERED_ID",
+    "lmhead_probe_mfma", "workspace_region", "WS_NV", "WS_ROW_SLOT", "WS_TOK_C", "WS_GATHERED_ID",
 ]

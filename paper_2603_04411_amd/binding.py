@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "lmhead_logprob_fwd", "lmhead_logprob_bwd", "lmhead_multi_workspace_bytes", "lmhead_logprob_fwd_multi",
     "group_advantage",
     "lmhead_loss_workspace_bytes", "grpo_loss", "grpo_loss_noalloc", "flowrl_tb_loss", "ce_loss", "lmhead_check",
-    "lmhead_timing_enable", "lmhead_timing_read", "lmhead_workspace_region",
+    "lmhead_timing_enable", "lmhead_timing_read", "lmhead_workspace_region", "lmhead_probe_mfma",
 ]
 
 ERRORS = {
@@ -99,6 +99,8 @@ def load_library():
     lib.lmhead_check.argtypes = [vp, vp]
     lib.lmhead_workspace_region.restype = C.c_int
     lib.lmhead_workspace_region.argtypes = [dp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+    lib.lmhead_probe_mfma.restype = C.c_int
+    lib.lmhead_probe_mfma.argtypes = [vp, sz, vp, sz, i32, i32, vp]
     lib.lmhead_timing_enable.restype = C.c_int
     lib.lmhead_timing_enable.argtypes = [C.c_int]
     lib.lmhead_timing_read.restype = C.c_int
@@ -223,6 +225,12 @@ def ce_loss(logp, lens, R, T, loss, g_logp, ws) -> None:
 def lmhead_check(ws) -> int:
     """Synchronises the current stream; returns 0 or the (negative) sticky device status."""
     return int(load_library().lmhead_check(_ptr(ws), _stream()))
+
+
+def lmhead_probe_mfma(operands, sink, workgroups: int, iters: int) -> None:
+    rc = load_library().lmhead_probe_mfma(_ptr(operands), operands.numel() * operands.element_size(), _ptr(sink),
+                                          sink.numel() * sink.element_size(), workgroups, iters, _stream())
+    _check(rc, "lmhead_probe_mfma")
 
 
 def lmhead_timing_enable(on: bool) -> None:

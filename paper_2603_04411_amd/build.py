@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblmhead.so")
-SOURCES = ["lmhead_api.hip", "lmhead_aux.hip", "lmhead_loss.hip", "lmhead_gemm.hip",
+SOURCES = ["lmhead_api.hip", "lmhead_aux.hip", "lmhead_loss.hip", "lmhead_gemm.hip", "lmhead_probe.hip",
            "dynakv_api.hip", "dynakv_aux.hip", "dynakv_gemm.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -255,6 +255,10 @@ hipError_t launch_flowrl(const float* lp, const float* lr, const float* reward, 
                          const int32_t* len, int P, int G, int T, float beta, float* loss,
                          float* g, float* gz, float* resid, float* ws, hipStream_t s);
 
+// Bare matrix-core loop on register operands (measurement aid): `workgroups` x 4 wavefronts, `iters` x 2^20
+// flop each; operands: 256 bytes per thread, sink: one float per thread.
+hipError_t launch_mfma_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t s);
+
 constexpr int kLossSlotsPerBlock = 2048;
 
 // grpo_loss_noalloc keeps its block partials (four floats per block of kLossSlotsPerBlock slots of one

@@ -399,6 +399,17 @@ int lmhead_check(void* ws, void* stream) {
   return h.err != 0 ? LMHEAD_E_RANGE : LMHEAD_OK;
 }
 
+int lmhead_probe_mfma(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes,
+                      int32_t workgroups, int32_t iters, void* stream) {
+  if (!operands || !sink) return LMHEAD_E_NULL;
+  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return LMHEAD_E_SHAPE;
+  if (!aligned16(operands)) return LMHEAD_E_ALIGN;
+  const size_t threads = (size_t)workgroups * 256;
+  if (operand_bytes < threads * 256 || sink_bytes < threads * 4) return LMHEAD_E_WORKSPACE;
+  LM_TRY(launch_mfma_probe(operands, sink, workgroups, iters, static_cast<hipStream_t>(stream)));
+  return LMHEAD_OK;
+}
+
 int lmhead_timing_enable(int on) {
   if (on && g_timing.created == 0) {
     for (int i = 0; i < kTimingPool; ++i) {

@@ -336,3 +336,16 @@ def test_fp32_hidden_size_multiple_of_32():
     cfg = wl.CONFIGS[0].scaled(P=2, G=2, T=24, d=96, V=777)
     r = _grpo_chain(cfg, small_inputs(cfg))
     assert r["err_dH"] < 1e-4 and r["err_dW"] < 1e-4
+
+
+def test_mfma_probe_does_the_flops_it_reports():
+    """The measurement aid behind the benchmark's `ceiling` figures: with all-ones operands every accumulator
+    element grows by K = 32 per MFMA, so a thread's 64 blocks x 4 elements sum to 8192 x iters."""
+    import torch
+    import paper_2603_04411_amd as L
+    wgs, iters = 3, 5
+    ops = torch.ones(wgs * 256 * 128, dtype=torch.bfloat16, device="cuda")
+    sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+    L.lmhead_probe_mfma(ops, sink, wgs, iters)
+    torch.cuda.synchronize()
+    assert bool((sink == 8192.0 * iters).all())

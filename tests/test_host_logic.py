@@ -158,6 +158,13 @@ def test_compute_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert c(p, p, 0, 32, p, p, p, lws, None) == -2
     assert c(p, p, 8, 32, p, p, p, 4, None) == -5
     assert lib.lmhead_check(None, None) == -1
+    probe = lib.lmhead_probe_mfma
+    assert probe(None, 1 << 20, p, 1 << 20, 4, 10, None) == -1
+    assert probe(p, 1 << 20, p, 1 << 20, 0, 10, None) == -2
+    assert probe(p, 1 << 20, p, 1 << 20, 4, 0, None) == -2
+    assert probe(p + 4, 1 << 20, p, 1 << 20, 4, 10, None) == -4
+    assert probe(p, 4 * 256 * 256 - 1, p, 1 << 20, 4, 10, None) == -5
+    assert probe(p, 1 << 20, p, 4 * 256 * 4 - 1, 4, 10, None) == -5
     ms, n = C.c_double(), C.c_int64()
     assert lib.lmhead_timing_read(14, C.byref(ms), C.byref(n)) == -2
     assert lib.lmhead_timing_read(0, None, C.byref(n)) == -1
