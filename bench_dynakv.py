@@ -38,18 +38,26 @@ BWD_KINDS = {4: "kv_gemm_kernel<spectral projection>", 5: "kv_gemm_kernel<gate l
 TRAFFIC_KEYS = {4: "spectral_projection", 5: "gate_logits", 6: "kv_mask_kernel", 7: "reconstruction"}
 
 
-def recorded_traffic(kind: int):
-    """HBM-side bytes per launch of one kernel kind for kv_configs[2], as recorded from two rocprofv3
-    --pmc runs (FETCH_SIZE, WRITE_SIZE; scaling stated in the file).  None if absent."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_dynakv.md")
+def recorded_traffic(kind: int, config: int):
+    """(bytes per launch, source) of one kernel kind: scaled FETCH_SIZE + WRITE_SIZE from the two rocprofv3
+    --pmc runs summarised under profiles/ -- used only if that summary says it was measured for this
+    workload and these kernel sources (rocprofv3 cannot run inside the timed process); else (None, reason)."""
+    from bench import kernel_sources_sha
+    name = "hbm_traffic_bench_dynakv.md"
+    want = f"kv_config={config} csrc_sha={kernel_sources_sha()}"
+    value, valid_for = None, None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             parts = line.split()
             if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == TRAFFIC_KEYS[kind]:
-                return float(parts[2])
+                value = float(parts[2])
+            if parts and parts[0] == "measured_for":
+                valid_for = " ".join(parts[1:])
     except OSError:
-        pass
-    return None
+        return None, f"no profiles/{name}"
+    if valid_for != want:
+        return None, f"profiles/{name} was measured for [{valid_for}], this run is [{want}]"
+    return value, f"profiles/{name}"
 
 
 def log(msg: str) -> None:
@@ -270,13 +278,15 @@ def main(argv=None) -> int:
             kinds.append({"kernel": name, "kind": kind, "launches": int(cnt), "avg_ms": avg, "bound": "mfma",
                           "tflops": rate, "frac": rate / peak})
     dom = max(kinds, key=lambda e: e["avg_ms"])
-    traffic = recorded_traffic(dom["kind"]) if args.config == 2 else None
+    traffic, traffic_source = recorded_traffic(dom["kind"], args.config)
     if dom["bound"] == "mfma":
         roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak,
-                    "unit": "TFLOP/s", "frac": dom["frac"], "traffic": traffic, "avg_launch_ms": dom["avg_ms"]}
+                    "unit": "TFLOP/s", "frac": dom["frac"], "traffic": traffic, "traffic_source": traffic_source,
+                    "avg_launch_ms": dom["avg_ms"]}
     else:
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": dom["frac"], "traffic": traffic, "avg_launch_ms": dom["avg_ms"]}
+                    "unit": "GB/s", "frac": dom["frac"], "traffic": traffic, "traffic_source": traffic_source,
+                    "avg_launch_ms": dom["avg_ms"]}
 
     cpu = None
     if args.cpu_rows > 0:

@@ -143,11 +143,6 @@ __device__ inline void lds_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// Default for run()'s at_drain argument: nothing to do.
-struct NoDrainHook {
-  __host__ __device__ inline void operator()() const {}
-};
-
 // kLeadB selects which operand goes first round the LDS ring (see run()).
 // kMaskB: every B row has its own K extent (ragged rows); loads past it fetch zeros (see run()).
 template <typename E, int BM_, int BN_, int WGM_, int WGN_, bool kLeadB = false, bool kMaskB = false>
@@ -223,69 +218,12 @@ struct GemmTile {
   // kLeadB selects which operand goes first round the ring, i.e. which one is loaded a full K-step
   // or more ahead (the other has half a K-step to a K-step): false = A, true = B.  Give the long
   // lead to the operand that misses L2 more often (the one fewer concurrent workgroups share).
-  // prefetched: the caller has already issued K-step 0 of both operands with prefetch() (same
-  // pointers and offsets) and nothing has touched ring slots 0 and 1 since.
-  // at_drain: called once, by every wave, when the last two K-steps begin (all loads of the tile have
-  // been issued by then): the place to request what only the epilogue needs, so that its latency
-  // is covered by the last K-steps without the values occupying registers during the whole loop.
-  template <typename F>
   __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                     const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                    int ksteps, char* lds, bool prefetched, F at_drain) {
+                                    int ksteps, char* lds) {
     static_assert(!kMaskB, "ragged rows need their limits");
     const int none[B_LD] = {};
-    run_rows_hook(acc, A, offA, B, offB, none, 0x7fffffffu, ksteps, lds, prefetched, at_drain);
-  }
-  __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
-                                    const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                    int ksteps, char* lds, bool prefetched = false) {
-    run(acc, A, offA, B, offB, ksteps, lds, prefetched, NoDrainHook());
-  }
-
-  // Ring slots 0 and 1 occupy, in every 5 KB row group of LDS, the first 2 KB; the remaining 3 KB
-  // (slots 2 to 4) of the kGroups groups are what a caller may use between prefetch() and run().
-  static constexpr int kGroups = SLOT / SSTR;           // row groups of a slot (32)
-  static constexpr int kFreeOff = 2 * SSTR;             // first free byte of a group after prefetch()
-  static constexpr int kFreeBytes = (NSLOT - 2) * SSTR; // free bytes per group (3 KB)
-
-  // Issues the loads of K-step 0 of both operands (the first two units of the ring, slots 0 and 1)
-  // and returns without waiting: a persistent workgroup calls this for its NEXT tile as soon as the
-  // main loop of the current one has returned, so that the tile's first operands travel while the
-  // epilogue runs; the next run() is then called with prefetched = true.  Between the two calls
-  // LDS bytes [g * GSTR, g * GSTR + kFreeOff) of every row group g must not be written.
-  __device__ static inline void prefetch(const char* __restrict__ A, const uint32_t (&offA)[A_LD],
-                                         const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                         const int (&limB)[B_LD], uint32_t bytesB, char* lds) {
-    typedef __attribute__((address_space(3))) void* lptr_t;
-    const int w = wave();
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(A), 0, 0x7fffffff, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
-        uniform_ptr(B), 0, (int)__builtin_amdgcn_readfirstlane(bytesB), 0x00020000);
-    const int slotA = kLeadB ? 1 : 0, slotB = kLeadB ? 0 : 1;
-#pragma unroll
-    for (int q = 0; q < A_LD; ++q)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(lds + slotA * SSTR + (w * A_LD + q) * GSTR), 16, offA[q], 0, 0, 0);
-#pragma unroll
-    for (int q = 0; q < B_LD; ++q) {
-      uint32_t vo = offB[q];
-      if constexpr (kMaskB) vo = (0 < limB[q]) ? vo : 0x80000000u;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(lds + slotB * SSTR + (w * B_LD + q) * GSTR), 16, vo, 0, 0, 0);
-    }
-  }
-  __device__ static inline void prefetch(const char* __restrict__ A, const uint32_t (&offA)[A_LD],
-                                         const char* __restrict__ B, const uint32_t (&offB)[B_LD], char* lds) {
-    static_assert(!kMaskB, "ragged rows need their limits");
-    const int none[B_LD] = {};
-    prefetch(A, offA, B, offB, none, 0x7fffffffu, lds);
-  }
-
-  // The tile pointers are wave-uniform by construction; saying so explicitly keeps the buffer
-  // descriptors in SGPRs (otherwise every load is wrapped in a readfirstlane loop).
-  __device__ static inline void* uniform_ptr(const char* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+    run_rows(acc, A, offA, B, offB, none, 0x7fffffffu, ksteps, lds);
   }
 
   // Same, with B given as one buffer of `bytesB` bytes (at most 2^31) that holds rows of differing
@@ -296,15 +234,7 @@ struct GemmTile {
   // LDS without touching memory.
   __device__ static inline void run_rows(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                          const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                         const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds,
-                                         bool prefetched = false) {
-    run_rows_hook(acc, A, offA, B, offB, limB, bytesB, ksteps, lds, prefetched, NoDrainHook());
-  }
-  template <typename F>
-  __device__ static inline void run_rows_hook(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
-                                              const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                              const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds,
-                                              bool prefetched, F at_drain) {
+                                         const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds) {
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int w = wave();
     const int l = lane();
@@ -318,6 +248,14 @@ struct GemmTile {
     static_assert(A_LD % NPART == 0 && B_LD % NPART == 0, "loads split evenly over the regions");
     // Raw buffer descriptors over each operand tile: base = the tile's first row, 2 GiB window,
     // so a load needs one 32-bit VGPR offset (row * pitch + byte) and a scalar K offset.
+    // The tile pointers are wave-uniform by construction; saying so explicitly keeps the
+    // descriptors in SGPRs (otherwise every load is wrapped in a readfirstlane loop).
+    auto uniform_ptr = [](const char* p) {
+      const uint64_t v = reinterpret_cast<uint64_t>(p);
+      const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+      const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+      return reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+    };
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(A), 0, 0x7fffffff, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
         uniform_ptr(B), 0, (int)__builtin_amdgcn_readfirstlane(bytesB), 0x00020000);
@@ -415,17 +353,12 @@ struct GemmTile {
       if constexpr (kLeadB) read_frags(cy, cx, s, buf); else read_frags(cx, cy, s, buf);
     };
 
-    if (ksteps <= 0) {
-      at_drain();
-      return;
-    }
+    if (ksteps <= 0) return;
     if constexpr (NSUB == 4) {
       // ring state: slots of X(ks) and Y(ks); unit u lives in slot u % NSLOT
       int sA = 0, sB = 1;
-      if (!prefetched) {
-        issue_x(0, 0, 0); issue_x(0, 0, 1);
-        issue_y(0, 1, 0); issue_y(0, 1, 1);
-      }
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
       if (ksteps > 1) {
         issue_x(1, 2, 0); issue_x(1, 2, 1);
         issue_y(1, 3, 0);
@@ -476,7 +409,6 @@ struct GemmTile {
         sB = sB1;
       }
       // drain: the last two K-steps (the first half of Y(ks+1) is already under way)
-      at_drain();
       for (; ks < ksteps; ++ks) {
         const char* ca = lds + sA * SSTR;
         const char* cb = lds + sB * SSTR;
@@ -555,10 +487,8 @@ struct GemmTile {
         }
       };
       int sX = 0, sY = 1;
-      if (!prefetched) {
-        issue_x(0, 0, 0); issue_x(0, 0, 1);
-        issue_y(0, 1, 0); issue_y(0, 1, 1);
-      }
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
       if (ksteps > 1) {
         issue_x(1, 2, 0); issue_x(1, 2, 1);
         issue_y(1, 3, 0); issue_y(1, 3, 1);
@@ -606,7 +536,6 @@ struct GemmTile {
         sY = next_slot(sY, 2);
       }
       // drain: the last two K-steps (their tiles were all requested above or in the prologue)
-      at_drain();
       for (; ks < ksteps; ++ks) {
         const char* cx = lds + sX * SSTR;
         const char* cy = lds + sY * SSTR;
@@ -659,10 +588,8 @@ struct GemmTile {
         __builtin_amdgcn_sched_barrier(0);
       };
       int sX = 0, sY = 1;
-      if (!prefetched) {
-        issue_x(0, 0, 0); issue_x(0, 0, 1);
-        issue_y(0, 1, 0); issue_y(0, 1, 1);
-      }
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
       if (ksteps > 1) {
         issue_x(1, 2, 0); issue_x(1, 2, 1);
         issue_y(1, 3, 0); issue_y(1, 3, 1);
@@ -707,7 +634,6 @@ struct GemmTile {
         sY = sY1;
       }
       // drain: the last two K-steps (their tiles were all requested above or in the prologue)
-      at_drain();
       for (; ks < ksteps; ++ks) {
         const char* cx = lds + sX * SSTR;
         const char* cy = lds + sY * SSTR;
