@@ -50,6 +50,8 @@ struct WsLayout {
   int ksplit;       // dH: slices of the contraction per output tile (> 1 only when the tile grid
                     // alone would leave most of the chip idle); partial tiles go to dHpart
   size_t dHpart;
+  size_t dWpart;        // partial tiles of the dW launches that split a remainder of vocabulary tiles
+  size_t dWpart_bytes;
   size_t hdr, cu_len, row_slot, tok_c, gid, g_c, lse_c, zy, part, Hc, HcT, WT, dZ, dZT, Hc8, W8, total;
 };
 
@@ -125,6 +127,11 @@ static inline WsLayout make_layout(const lmhead_desc* d, int npol = 1) {
     const bool need = ks > 1 || (d->flags & LMHEAD_FLAG_DH_BF16) != 0;
     L.dHpart = take(need ? (size_t)ks * L.Ncap * L.dp * 4 : 0);
   }
+  // dW: the vocabulary tiles of a chunk that would start a mostly empty round of workgroups are contracted
+  // in slices instead (see lmhead_logprob_bwd); slices x rows x d of them never exceed compute units x 64 Ki floats
+  L.dWpart_bytes = (size_t)128 << 20;
+  if ((size_t)L.Vc * L.dp * 4 * 8 < L.dWpart_bytes) L.dWpart_bytes = (size_t)L.Vc * L.dp * 4 * 8;
+  L.dWpart = take(L.dWpart_bytes);
   L.ld8 = d->d + 128;
   const bool fp8 = (d->flags & LMHEAD_FLAG_FP8_LOGITS) != 0;
   L.Hc8 = take(fp8 ? (size_t)L.Ncap * L.ld8 : 0);
@@ -165,6 +172,7 @@ struct FwdArgs {
   const int32_t* tok_c;
   const WsHeader* hdr;
   float* part;         // [npol][3][ntiles][Ncap]: per-tile (max, sum exp, sum exp*z) of each row
+  bool want_entropy;   // false: sum exp*z is not accumulated (its plane holds zeros)
   float* zy;           // [npol][Ncap]
   int32_t* gid;        // [npol][Ncap]: vocabulary column whose logit was captured as the target's
   float zscale;        // logits = accumulator * zscale (1, or 2^-(e_H + e_W) for e4m3 operands)
@@ -231,11 +239,14 @@ struct GemmTArgs {
   bool part_accumulate;
 };
 
-// out[rowmap(n)][m] (+)= sum_s part[s][n][m] for n < header.nv, m < M, slices summed in order.
+// out[row(n)][m] (+)= sum_s part[s][n][m] for n < n_valid, m < M, slices summed in order.  With a row map:
+// row(n) = rowmap[n] and n_valid = header.nv; without: row(n) = row_base + n and n_valid = n_cap.
 // out is float, or bf16 when out_bf16 (then accumulate must be false).
 hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
                                 const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, void* out, int64_t ldo,
-                                bool accumulate, bool out_bf16, hipStream_t s);
+                                bool accumulate, bool out_bf16, hipStream_t s, int64_t row_base = 0);
+// Compute units of the current device (asked of the runtime once per device; 256 if it cannot be asked).
+int device_compute_units();
 // role: -1 = by use (dW when k_from_nv, else dH); 2 = parameter gradient of the KV gate (distinct kernel name).
 hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s, int role = -1);
 

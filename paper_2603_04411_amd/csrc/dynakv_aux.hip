@@ -467,49 +467,6 @@ __global__ __launch_bounds__(256) void kv_pad_copy_kernel(const char* __restrict
   *reinterpret_cast<uint4*>(out + r * out_pitch + c) = v;
 }
 
-// out[c][r] = in[r][c] for r < rows, c < cols, zero up to [cols_p x rows_p]: 64 x 64 tiles with 16-byte
-// global accesses on both sides.  Rows of the source go to LDS as they are (padded pitch); each thread
-// then gathers the 16 bytes of one output chunk (consecutive r of one column) from LDS.
-// Requires 16-byte aligned rows on both sides and cols, cols_p, rows_p multiples of 64.
-template <typename T>
-__global__ __launch_bounds__(256) void kv_transpose_kernel(const T* __restrict__ in, int64_t ld_in, int64_t rows,
-                                                           int cols, T* __restrict__ out, int64_t ld_out) {
-  constexpr int VEC = 16 / sizeof(T);         // elements per 16-byte chunk
-  constexpr int CPR = 64 / VEC;               // chunks per tile row
-  constexpr int PITCH = 64 + 4 / sizeof(T);   // elements; keeps rows 4-byte aligned and the gather conflict-free
-  __shared__ __attribute__((aligned(16))) T tile[64 * PITCH];
-  const int64_t r0 = (int64_t)blockIdx.x * 64;
-  const int c0 = blockIdx.y * 64;
-#pragma unroll
-  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
-    const int id = pass * 256 + threadIdx.x;
-    const int rr = id / CPR, cc = id % CPR;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r0 + rr < rows && c0 < cols) v = *reinterpret_cast<const uint4*>(in + (r0 + rr) * ld_in + c0 + cc * VEC);
-    uint32_t* dst = reinterpret_cast<uint32_t*>(tile + rr * PITCH + cc * VEC);
-    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
-    const int id = pass * 256 + threadIdx.x;
-    const int c = id / CPR, rc = id % CPR;
-    T e[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) e[i] = tile[(rc * VEC + i) * PITCH + c];
-    uint4 v;
-    if constexpr (sizeof(T) == 2) {
-      v.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-      v.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
-      v.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
-      v.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
-    } else {
-      v = make_uint4(e[0], e[1], e[2], e[3]);
-    }
-    *reinterpret_cast<uint4*>(out + (int64_t)(c0 + c) * ld_out + r0 + rc * VEC) = v;
-  }
-}
-
 // ---- ragged store ---------------------------------------------------------------------------
 
 __device__ inline int seg_len(int k, int d, int& bad) {
@@ -874,14 +831,8 @@ hipError_t launch_kv_pad_copy(int dtype, const void* in, int64_t ld_in, int rows
 
 hipError_t launch_kv_transpose(int dtype, const void* in, int64_t ld_in, int64_t rows, int cols, void* out,
                                int64_t ld_out, int64_t rows_p, int cols_p, hipStream_t s) {
-  const dim3 grid((unsigned)(rows_p / 64), (unsigned)(cols_p / 64));
-  if (dtype == LMHEAD_BF16)
-    hipLaunchKernelGGL(kv_transpose_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), ld_in,
-                       rows, cols, static_cast<uint16_t*>(out), ld_out);
-  else
-    hipLaunchKernelGGL(kv_transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t*>(in), ld_in,
-                       rows, cols, static_cast<uint32_t*>(out), ld_out);
-  return hipGetLastError();
+  // rows 16-byte aligned and extents multiples of 64 here: takes the 16-byte-access kernel
+  return launch_transpose(dtype, in, ld_in, rows, cols, false, nullptr, out, ld_out, rows_p, cols_p, s);
 }
 
 hipError_t launch_kv_store(int dtype, const void* xt, const int32_t* k, int64_t n, int d, int64_t off_base,

@@ -148,6 +148,7 @@ static int forward(const lmhead_desc* desc, const void* H, const void* const* W,
   fa.tok_c = w.at<int32_t>(L.tok_c);
   fa.hdr = hdr;
   fa.part = w.at<float>(L.part);
+  fa.want_entropy = entropy != nullptr;
   fa.zy = w.at<float>(L.zy);
   fa.gid = w.at<int32_t>(L.gid);
   {
@@ -310,13 +311,46 @@ int lmhead_logprob_bwd(const lmhead_desc* desc, const void* H, const void* W, co
     wa.out = dW;
     wa.ldo = desc->d;
     wa.accumulate = (desc->flags & LMHEAD_FLAG_ACCUM_DW) != 0;
-    wa.n_tiles_cap = ntiles;
     wa.hdr = hdr;
-    wa.ksplit = 1;
-    wa.part = nullptr;
+    // Every output tile is one workgroup and the compute units take them a round at a time.  The vocabulary
+    // tiles of this chunk that would start a mostly empty last round (with d / 256 tiles along d, 16 of them
+    // fill the 256 compute units at d = 4096; a chunk of 18 leaves 2) are launched apart, their contraction
+    // over the tokens cut into as many slices as make that round full; the slices are summed in a fixed order.
+    const int m_tiles = (int)(L.dp / kTile), cus = device_compute_units();
+    int t_rem = 0, ks = 1;
+    if (m_tiles <= cus && cus % m_tiles == 0) {
+      t_rem = ntiles % (cus / m_tiles);
+      ks = t_rem > 0 ? cus / (t_rem * m_tiles) : 1;
+      if (ks > 8) ks = 8;
+      if (ks < 2 || (size_t)ks * t_rem * kTile * L.dp * 4 > L.dWpart_bytes) t_rem = 0;
+    }
+    const int t_main = ntiles - t_rem;
     {
       TimedLaunch tl(3, s);
-      LM_TRY(launch_gemm_t(dt, wa, s));
+      if (t_main > 0) {
+        GemmTArgs m = wa;
+        m.n_limit = wa.n_limit < (int64_t)t_main * kTile ? wa.n_limit : (int64_t)t_main * kTile;
+        m.n_tiles_cap = t_main;
+        m.ksplit = 1;
+        m.part = nullptr;
+        LM_TRY(launch_gemm_t(dt, m, s));
+      }
+      if (t_rem > 0) {
+        GemmTArgs r = wa;
+        r.B = w.at<char>(L.dZT) + (size_t)t_main * kTile * L.ldZT * L.esz;
+        r.n_limit = wa.n_limit - (int64_t)t_main * kTile;
+        r.n_tiles_cap = t_rem;
+        r.ksplit = ks;
+        r.part = w.at<float>(L.dWpart);
+        r.part_ld = L.dp;
+        r.part_slice = (int64_t)t_rem * kTile * L.dp;
+        r.part_accumulate = false;
+        if (r.n_limit > 0) {
+          LM_TRY(launch_gemm_t(dt, r, s));
+          LM_TRY(launch_splitk_reduce(r.part, ks, r.part_slice, r.part_ld, desc->d, nullptr, hdr, r.n_limit, dW,
+                                      desc->d, wa.accumulate, false, s, c0 + (int64_t)t_main * kTile));
+        }
+      }
     }
   }
   return LMHEAD_OK;

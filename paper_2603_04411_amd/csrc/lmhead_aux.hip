@@ -5,6 +5,8 @@
 // over O(N d + V d) bytes.
 #include <math.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace lmhead {
@@ -176,6 +178,53 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
   }
 }
 
+// The same transposition for the common case of 16-byte aligned rows on both sides and extents that are
+// multiples of 64: 64 x 64 tiles with 16-byte global accesses on both sides (the element-wise kernel above
+// moves 2 or 4 bytes per lane and runs at about half the rate).  Rows of the source go to LDS as they are
+// (padded pitch); each thread then gathers the 16 bytes of one output chunk (consecutive r of one column).
+template <typename T>
+__global__ __launch_bounds__(256) void transpose16_kernel(const T* __restrict__ in, int64_t ld_in, int64_t rows_fixed,
+                                                          int cols, int rows_from_nv, const WsHeader* __restrict__ hdr,
+                                                          T* __restrict__ out, int64_t ld_out) {
+  constexpr int VEC = 16 / sizeof(T);         // elements per 16-byte chunk
+  constexpr int CPR = 64 / VEC;               // chunks per tile row
+  constexpr int PITCH = 64 + 4 / sizeof(T);   // elements; keeps rows 4-byte aligned and the gather conflict-free
+  __shared__ __attribute__((aligned(16))) T tile[64 * PITCH];
+  const int64_t rows = rows_from_nv ? (int64_t)hdr->nv : rows_fixed;
+  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  // nothing beyond the tile-padded valid extent is ever read by the contractions
+  if (rows_from_nv && r0 >= (rows + kTile - 1) / kTile * kTile) return;
+#pragma unroll
+  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
+    const int id = pass * 256 + threadIdx.x;
+    const int rr = id / CPR, cc = id % CPR;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r0 + rr < rows && c0 < cols) v = *reinterpret_cast<const uint4*>(in + (r0 + rr) * ld_in + c0 + cc * VEC);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(tile + rr * PITCH + cc * VEC);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 64 * CPR / 256; ++pass) {
+    const int id = pass * 256 + threadIdx.x;
+    const int c = id / CPR, rc = id % CPR;
+    T e[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) e[i] = tile[(rc * VEC + i) * PITCH + c];
+    uint4 v;
+    if constexpr (sizeof(T) == 2) {
+      v.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
+      v.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
+      v.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
+      v.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
+    } else {
+      v = make_uint4(e[0], e[1], e[2], e[3]);
+    }
+    *reinterpret_cast<uint4*>(out + (int64_t)(c0 + c) * ld_out + r0 + rc * VEC) = v;
+  }
+}
+
 // ---- 8-bit operand copies ---------------------------------------------------------------
 
 // One wavefront per row: out = e4m3(in * scale), eight values per lane and pass.  The hardware
@@ -247,7 +296,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
       if (mc == -__builtin_huge_valf()) continue;
       const float w = __builtin_amdgcn_exp2f((mc - m) * kLog2e);
       s = fmaf(part[plane + idx], w, s);
-      tt = fmaf(part[2 * plane + idx], w, tt);
+      if (ent) tt = fmaf(part[2 * plane + idx], w, tt);
     }
     o_lse = m + __builtin_amdgcn_logf(s) * kLn2;
     o_lp = zy[k] - o_lse;
@@ -265,11 +314,12 @@ template <typename TO>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int ksplit,
                                                             int64_t part_slice, int64_t part_ld, int M,
                                                             const int32_t* __restrict__ rowmap,
-                                                            const WsHeader* __restrict__ hdr,
-                                                            TO* __restrict__ out, int64_t ldo, int accumulate) {
+                                                            const WsHeader* __restrict__ hdr, int64_t n_cap,
+                                                            int64_t row_base, TO* __restrict__ out, int64_t ldo,
+                                                            int accumulate) {
   const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (n >= hdr->nv) return;
-  const int64_t row = rowmap[n];
+  if (n >= (rowmap ? (int64_t)hdr->nv : n_cap)) return;
+  const int64_t row = rowmap ? (int64_t)rowmap[n] : row_base + n;
   if (row < 0) return;
   const int lane = threadIdx.x & 63;
   for (int m = lane * 4; m < M; m += 256) {
@@ -338,6 +388,19 @@ hipError_t launch_transpose(int dtype, const void* in, int64_t ld_in, int64_t ro
                             bool rows_from_nv, const WsHeader* hdr, void* out, int64_t ld_out,
                             int64_t rows_p, int64_t cols_p, hipStream_t s) {
   const dim3 grid((unsigned)((rows_p + 63) / 64), (unsigned)((cols_p + 63) / 64));
+  const int esz = dtype == LMHEAD_BF16 ? 2 : 4;
+  const bool wide = cols % 64 == 0 && cols_p % 64 == 0 && rows_p % 64 == 0 && (ld_in * esz) % 16 == 0 &&
+                    (ld_out * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(in) & 15u) == 0 &&
+                    (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+  if (wide) {
+    if (dtype == LMHEAD_BF16)
+      hipLaunchKernelGGL(transpose16_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), ld_in,
+                         rows_cap, cols, rows_from_nv ? 1 : 0, hdr, static_cast<uint16_t*>(out), ld_out);
+    else
+      hipLaunchKernelGGL(transpose16_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t*>(in), ld_in,
+                         rows_cap, cols, rows_from_nv ? 1 : 0, hdr, static_cast<uint32_t*>(out), ld_out);
+    return hipGetLastError();
+  }
   if (dtype == LMHEAD_BF16) {
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(in), ld_in, rows_cap, cols, rows_from_nv ? 1 : 0,
@@ -366,15 +429,28 @@ hipError_t launch_quantize_e4m3(int dtype, const void* in, int64_t ld_in, int64_
 
 hipError_t launch_splitk_reduce(const float* part, int ksplit, int64_t part_slice, int64_t part_ld, int M,
                                 const int32_t* rowmap, const WsHeader* hdr, int64_t n_cap, void* out, int64_t ldo,
-                                bool accumulate, bool out_bf16, hipStream_t s) {
+                                bool accumulate, bool out_bf16, hipStream_t s, int64_t row_base) {
   const dim3 grid((unsigned)((n_cap + 3) / 4));
   if (out_bf16)
     hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, grid, dim3(256), 0, s, part, ksplit, part_slice, part_ld, M,
-                       rowmap, hdr, static_cast<__bf16*>(out), ldo, 0);
+                       rowmap, hdr, n_cap, row_base, static_cast<__bf16*>(out), ldo, 0);
   else
     hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, dim3(256), 0, s, part, ksplit, part_slice, part_ld, M,
-                       rowmap, hdr, static_cast<float*>(out), ldo, accumulate ? 1 : 0);
+                       rowmap, hdr, n_cap, row_base, static_cast<float*>(out), ldo, accumulate ? 1 : 0);
   return hipGetLastError();
+}
+
+int device_compute_units() {
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> cus[kMaxDev];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 256;
+  int n = cus[dev].load(std::memory_order_acquire);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus[dev].store(n, std::memory_order_release);
+  }
+  return n;
 }
 
 hipError_t launch_finalize(const float* part, const float* zy, int nchunks, int64_t Ncap,

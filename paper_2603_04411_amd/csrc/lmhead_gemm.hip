@@ -149,8 +149,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     const float kz = kLog2e * zscale;
     constexpr int BPC = 16 / G::VB;            // blocks per group of 16 values
     static_assert(G::TM % BPC == 0, "groups of 16 values");
-    auto group_stats = [&](auto full_tag, int ic, int j, float& m_run, float& s_run, float& t_run) {
+    auto group_stats = [&](auto full_tag, auto ent_tag, int ic, int j, float& m_run, float& s_run, float& t_run) {
       constexpr bool kFull = decltype(full_tag)::value;
+      constexpr bool kEnt = decltype(ent_tag)::value;   // the third accumulator (sum exp * z) feeds the entropy only
       float z[16];
       bool ok[16];
 #pragma unroll
@@ -172,23 +173,24 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       for (int v = 0; v < 16; ++v) {
         const float e = fast_exp2(fmaf(z[v], kz, bias));   // exp2(-inf) = 0 on padding rows
         ss += e;
-        ts = fmaf(e, ok[v] ? z[v] : 0.f, ts);
+        if constexpr (kEnt) ts = fmaf(e, ok[v] ? z[v] : 0.f, ts);
       }
       s_run = fmaf(s_run, sc, ss);
-      t_run = fmaf(t_run, sc, ts * zscale);
+      if constexpr (kEnt) t_run = fmaf(t_run, sc, ts * zscale);
       m_run = mn;
       __builtin_amdgcn_sched_barrier(0);
     };
+    auto all_groups = [&](auto full_tag, auto ent_tag) {
+#pragma unroll
+      for (int j = 0; j < G::TN; ++j)
+#pragma unroll
+        for (int ic = 0; ic < G::TM / BPC; ++ic) group_stats(full_tag, ent_tag, ic, j, mr[j], sr[j], tr[j]);
+    };
+    const bool want_t = a.want_entropy && pol == 0;   // entropy is reported for the first weight matrix only
     if (m0 + G::BM <= a.V) {
-#pragma unroll
-      for (int j = 0; j < G::TN; ++j)
-#pragma unroll
-        for (int ic = 0; ic < G::TM / BPC; ++ic) group_stats(std::true_type{}, ic, j, mr[j], sr[j], tr[j]);
+      if (want_t) all_groups(std::true_type{}, std::true_type{}); else all_groups(std::true_type{}, std::false_type{});
     } else {
-#pragma unroll
-      for (int j = 0; j < G::TN; ++j)
-#pragma unroll
-        for (int ic = 0; ic < G::TM / BPC; ++ic) group_stats(std::false_type{}, ic, j, mr[j], sr[j], tr[j]);
+      if (want_t) all_groups(std::false_type{}, std::true_type{}); else all_groups(std::false_type{}, std::false_type{});
     }
   }
 
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     const size_t plane = (size_t)a.ntiles * a.Ncap;
     part[base] = m;
     part[plane + base] = s;
-    part[2 * plane + base] = t;
+    if (a.want_entropy && pol == 0) part[2 * plane + base] = t;
   }
 }
 
