@@ -305,7 +305,7 @@ def main() -> int:
     step_flops_model = flops_per_pass * 3                      # logits + dH + dW
 
     ceiling = None
-    if cfg.dtype == "bf16" and not args.no_ceiling:
+    if cfg.dtype == "bf16" and not args.fp8_logits and not args.no_ceiling:      # the probe is a bf16 loop
         ceiling = matrix_core_ceiling(L, torch)
         log(f"bare MFMA loop: {ceiling['mfma_loop_zeros_tflops']:.0f} TFLOP/s on zeros, "
             f"{ceiling['mfma_loop_random_tflops']:.0f} on random bf16")

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/lmhead.h"
 
 namespace lmhead {
@@ -314,5 +316,26 @@ struct TimedLaunch {
   do {                                             \
     if ((expr) != hipSuccess) return LMHEAD_E_HIP; \
   } while (0)
+
+// Raises a kernel's dynamic LDS limit to at least `bytes`.  The runtime is asked only when a launch needs more
+// than what it has already granted this kernel on the current device (the kernel is a template argument, so
+// each instantiation keeps its own record).
+template <auto kernel>
+inline hipError_t allow_lds(int bytes) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> granted[kMaxDev];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < kMaxDev;
+  if (tracked && granted[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) {
+    int seen = granted[dev].load(std::memory_order_relaxed);
+    while (seen < bytes && !granted[dev].compare_exchange_weak(seen, bytes, std::memory_order_release)) {
+    }
+  }
+  return e;
+}
 
 }  // namespace lmhead

@@ -785,8 +785,7 @@ static hipError_t launch_mask_bwd_t(const float* logits, const float* b, const v
   const int ng = (d + 255) / 256;
 #define KV_MASK_BWD(NG)                                                                                          \
   do {                                                                                                           \
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_mask_bwd_kernel<T, NG>),                 \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                    \
+    hipError_t e = allow_lds<kv_mask_bwd_kernel<T, NG>>((int)lds);                                               \
     if (e != hipSuccess) return e;                                                                               \
     hipLaunchKernelGGL((kv_mask_bwd_kernel<T, NG>), grid, dim3(256), lds, s, logits, b, x, gx, g_m, g_m_const, n, \
                        d, lit, g1, a1, dbpart);                                                                  \

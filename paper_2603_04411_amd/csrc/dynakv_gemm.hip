@@ -241,8 +241,7 @@ hipError_t launch_mode(const KvGemmArgs& a, hipStream_t s) {
   b.walk_len = (int)xcd_grid_size(mtiles, ntiles, kKvMapBy);
   const unsigned resident = (unsigned)compute_units() / kNumXcd * kNumXcd * kKvWgPerCu;   // LDS-bound
   const dim3 grid(b.walk_len < (int)resident ? (unsigned)b.walk_len : resident);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_gemm_kernel<E, Mode>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+  hipError_t e = allow_lds<kv_gemm_kernel<E, Mode>>(G::LDS_BYTES);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((kv_gemm_kernel<E, Mode>), grid, dim3(G::NT), G::LDS_BYTES, s, b);
   return hipGetLastError();

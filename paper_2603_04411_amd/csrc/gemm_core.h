@@ -4,7 +4,7 @@
 // gate logits and ragged reconstruction) are brought to the same form
 // C[m][n] = sum_k A[m][k] * B[n][k]  with both operands K-contiguous.
 // A workgroup owns a BM x BN tile of C; each wavefront owns a (BM/WGM) x (BN/WGN)
-// sub-tile built from 16x16 (bf16) or 32x32 (fp32, e4m3) MFMA blocks.
+// sub-tile built from 16x16 (bf16, e4m3) or 32x32 (fp32) MFMA blocks.
 //
 // Data movement: K is consumed 128 bytes per row per step (64 bf16 or 32 fp32), i.e. one
 // full cache line per row: the vector L1 moves one 128-byte line per ~2 clocks whether or
@@ -35,9 +35,13 @@
 //         operands a bare loop of it sustains 2092 TFLOP/s against 1843 for 32x32x16 (2447 / 2482 on
 //         zeros).  -DLMHEAD_BF16_BLOCK=32 builds the 32x32x16 form (four sub-steps) for comparison.
 //   fp32: NB = 32, the chunk's four floats feed four v_mfma_f32_32x32x2_f32, four sub-steps.
-//   e4m3: NB = 32, v_mfma_f32_32x32x64_f8f6f4, two chunks per lane and sub-step, two sub-steps.
-// Fragments are double-buffered in registers and the hand-over barrier is skewed so that the MFMAs
-// after it overlap the first fragment reads of the next K-step and the issue of the next loads.
+//   e4m3: NB = 16, v_mfma_f32_16x16x128_f8f6f4: one MFMA takes the whole K-step of a block pair, two chunks per
+//         lane (lane group g holds chunks 2g and 2g + 1).  Like the bf16 form it moves half the accumulator data
+//         of its 32x32 counterpart (32x32x64) per flop; measured on the 32x8x2048 workload the forward gained 6 %
+//         and the dZ kernel 5 % over a two-sub-step loop on 32x32x64.
+// Fragments are double-buffered in registers (e4m3: one set, refilled behind its last reader) and the hand-over
+// barrier is skewed so that the MFMAs after it overlap the first fragment reads of the next K-step and the
+// issue of the next loads.
 //
 // Accumulator layout of a block (NB * NB / 64 floats per lane); a lane owns one column n = l % NB:
 //   NB = 32: element v of lane l  <->  m = 8*(v/4) + 4*(l/32) + v%4   (16 values)
@@ -113,17 +117,23 @@ struct Elem<f32_tag> {
 template <>
 struct Elem<fp8_tag> {
   static constexpr int size = 1;
-  static constexpr int block = 32;
+  static constexpr int block = 16;
   static constexpr int frag_chunks = 2;   // 32 bytes = 32 e4m3 values of K per lane
   static constexpr int mfma_per_block = 1;
-  using acc_t = f32x16_t;
-  // v_mfma_f32_32x32x64_f8f6f4 with both formats e4m3 and no block scaling: lane l supplies row
-  // l % 32 and the 32 consecutive K values (l / 32) * 32 ... of a 64-wide K block (checked on
-  // gfx950 against an integer reference); the accumulator layout is that of the other 32x32 forms.
-  __device__ static inline void mma(f32x16_t& c, const u32x4_t (&a)[2], const u32x4_t (&b)[2]) {
+  using acc_t = f32x4_t;
+  // v_mfma_f32_16x16x128_f8f6f4 with both formats e4m3 (format code 0, the default) and no block scaling:
+  // one instruction consumes a whole 128-byte K-step of a 16-row block.  Lane l supplies row l % 16 and 32 of
+  // the 128 K values; which 32 does not matter as long as both operands are cut the same way (here: the
+  // 16-byte chunks 2 (l / 16) and 2 (l / 16) + 1 of the K-step).  An asm statement for the same reason as the
+  // bf16 form above: sixty-four 4-register accumulators that must stay in their AGPR tuples.
+  __device__ static inline void mma(f32x4_t& c, const i32x8_t& a, const i32x8_t& b) {
+    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+  }
+  // the same from two 16-byte chunks per operand (the form the generic fragment arrays hold)
+  __device__ static inline void mma(f32x4_t& c, const u32x4_t (&a)[2], const u32x4_t (&b)[2]) {
     const i32x8_t va = {(int)a[0].x, (int)a[0].y, (int)a[0].z, (int)a[0].w, (int)a[1].x, (int)a[1].y, (int)a[1].z, (int)a[1].w};
     const i32x8_t vb = {(int)b[0].x, (int)b[0].y, (int)b[0].z, (int)b[0].w, (int)b[1].x, (int)b[1].y, (int)b[1].z, (int)b[1].w};
-    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, c, 0, 0, 0, 0, 0, 0);
+    mma(c, va, vb);
   }
 };
 
@@ -173,7 +183,7 @@ struct GemmTile {
   static_assert(BM % (WGM * NB) == 0 && BN % (WGN * NB) == 0, "wave tiles are made of MFMA blocks");
   static_assert(NB == 32 || NB == 16, "block edge");
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile loads divide evenly");
-  static_assert(NSUB % 2 == 0, "fragment double-buffering assumes an even number of sub-steps");
+  static_assert(NSUB == 1 || NSUB % 2 == 0, "fragment double-buffering assumes an even number of sub-steps");
 
   using Block = typename Elem<E>::acc_t;
   using Acc = Block[TM][TN];
@@ -437,7 +447,7 @@ struct GemmTile {
         sA = sA1;
         sB = sB1;
       }
-    } else if constexpr (NB == 16) {
+    } else if constexpr (NB == 16 && FC == 1) {
       // bf16 on 16x16x32 blocks: two sub-steps per K-step, four lane groups with one chunk each.  Same
       // ring and the same four regions per K-step as below (32 MFMAs, eight fragment reads, four loads
       // each; hand-over barrier in the middle of the K-step), but the MFMAs are asm statements, so
@@ -557,9 +567,135 @@ struct GemmTile {
       }
       // the asm MFMAs' results are read by ordinary instructions next: let the last ones retire
       asm volatile("s_nop 15\n\ts_nop 15");
+    } else if constexpr (NB == 16 && FC == 2) {
+      // e4m3 on 16x16x128 blocks: ONE MFMA per block pair consumes the whole K-step (32 cycles each, 64 per
+      // K-step).  A second set of fragments does not fit the register file (2 x 128 registers), so there is
+      // one set, refilled behind the MFMAs that read it last: the A fragment of row block i right after the
+      // first MFMA of row block i + 1, the B fragment of column block j, during the last row block, right
+      // after MFMA (7, j + 1); the fragments of the last blocks (A[7], B[7]) arrive behind the first MFMA of
+      // the next K-step.  A refill is always placed behind the MFMA that FOLLOWS the register's last reader:
+      // when that one has been accepted by the matrix pipe the reader has long fetched its operands.
+      // Reads thus run one K-step ahead of the MFMAs: K-step c reads the tiles of K-step c + 1.  The barrier
+      // early in K-step c (behind its fourth MFMA) publishes the tiles of c + 1 and frees the two slots of c,
+      // which take Y(c + 2) and X(c + 3) at once: with X(c + 2) that is five units resident or in flight.
+      static_assert(NSUB == 1 && TM == TN && TM == 8 && A_LD == B_LD, "64 MFMAs per K-step");
+      i32x8_t ga[TM], gb[TN];
+      auto read_frag = [&](const char* slot, int r) {
+        const char* row = slot + row_off(r);
+        const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + (((2 * grp) ^ swz(r)) << 4));
+        const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + (((2 * grp + 1) ^ swz(r)) << 4));
+        const i32x8_t f = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        return f;
+      };
+      // slot bases of the A and B tiles of a K-step whose X / Y units sit in slots sx / sy
+      auto a_of = [&](int sx, int sy) { return lds + (kLeadB ? sy : sx) * SSTR; };
+      auto b_of = [&](int sx, int sy) { return lds + (kLeadB ? sx : sy) * SSTR; };
+      auto issue_a1 = [&](int ks, int slot, int q) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(lds + slot * SSTR + (w * A_LD + q) * GSTR), 16, offA[q],
+                                                 ks * KB, 0, 0);
+      };
+      auto issue_b1 = [&](int ks, int slot, int q) {
+        uint32_t vo = offB[q];
+        if constexpr (kMaskB) vo = (ks * KB < limB[q]) ? vo : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lptr_t)(lds + slot * SSTR + (w * B_LD + q) * GSTR), 16, vo,
+                                                 ks * KB, 0, 0);
+      };
+      auto issue_x1 = [&](int ks, int slot, int q) {
+        if constexpr (kLeadB) issue_b1(ks, slot, q); else issue_a1(ks, slot, q);
+      };
+      auto issue_y1 = [&](int ks, int slot, int q) {
+        if constexpr (kLeadB) issue_a1(ks, slot, q); else issue_b1(ks, slot, q);
+      };
+      // K-step c with X(c), Y(c) in slots sx, sy.  next: there is a K-step c + 1 (barrier and refills);
+      // ldy / ldx: Y(c + 2) / X(c + 3) exist and are requested; x2: X(c + 2) exists (it is then the only unit
+      // that may still be in flight at the barrier).
+      auto kstep = [&](int c, int sx, int sy, bool next, bool ldy, bool ldx, bool x2) {
+        const int sx1 = next_slot(sx, 2), sy1 = next_slot(sy, 2);
+        const char* a0 = a_of(sx, sy);
+        const char* b0 = b_of(sx, sy);
+        const char* a1 = a_of(sx1, sy1);
+        const char* b1 = b_of(sx1, sy1);
+#pragma unroll
+        for (int idx = 0; idx < TM * TN; ++idx) {
+          const int i = idx / TN, j = idx % TN;
+          Elem<E>::mma(acc[i][j], ga[i], gb[j]);
+          __builtin_amdgcn_sched_barrier(0);   // what follows stays behind this MFMA (see the refill rule above)
+          if (idx == 0) {
+            ga[TM - 1] = read_frag(a0, rA0 + (TM - 1) * NB);
+            gb[TN - 1] = read_frag(b0, rB0 + (TN - 1) * NB);
+          }
+          if (idx == 3 && next) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (x2) __builtin_amdgcn_s_waitcnt(wait_vm(A_LD)); else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+            __builtin_amdgcn_s_barrier();
+          }
+          if (next) {
+            if (idx >= 8 && idx % 8 == 0) ga[idx / 8 - 1] = read_frag(a1, rA0 + (idx / 8 - 1) * NB);
+            if (idx > 8 * (TM - 1)) gb[idx - 8 * (TM - 1) - 1] = read_frag(b1, rB0 + (idx - 8 * (TM - 1) - 1) * NB);
+            // sixteen loads behind every third MFMA from the barrier on: Y(c + 2) into the slot of X(c),
+            // X(c + 3) into the slot of Y(c)
+            if (idx >= 4 && (idx - 4) % 3 == 0 && (idx - 4) / 3 < 2 * A_LD) {
+              const int q = (idx - 4) / 3;
+              if (q < A_LD) {
+                if (ldy) issue_y1(c + 2, sx, q);
+              } else {
+                if (ldx) issue_x1(c + 3, sy, q - A_LD);
+              }
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      // prologue: X(0) Y(0) X(1) Y(1) X(2); wait for K-step 0's pair
+      issue_x(0, 0, 0); issue_x(0, 0, 1);
+      issue_y(0, 1, 0); issue_y(0, 1, 1);
+      if (ksteps > 1) {
+        issue_x(1, 2, 0); issue_x(1, 2, 1);
+        issue_y(1, 3, 0); issue_y(1, 3, 1);
+      }
+      if (ksteps > 2) {
+        issue_x(2, 4, 0); issue_x(2, 4, 1);
+        __builtin_amdgcn_s_waitcnt(wait_vm(3 * A_LD));
+      } else if (ksteps > 1) {
+        __builtin_amdgcn_s_waitcnt(wait_vm(2 * A_LD));
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      }
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i + 1 < TM; ++i) {
+        ga[i] = read_frag(a_of(0, 1), rA0 + i * NB);
+        gb[i] = read_frag(b_of(0, 1), rB0 + i * NB);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      int ks = 0;
+      // unrolled by the ring's period, so that every slot number is a constant (see the bf16 loop)
+      static_assert(NSLOT == 5, "unrolled by the ring's period");
+      for (; ks + 3 + (NSLOT - 1) < ksteps; ks += NSLOT) {
+        kstep(ks, 0, 1, true, true, true, true);
+        kstep(ks + 1, 2, 3, true, true, true, true);
+        kstep(ks + 2, 4, 0, true, true, true, true);
+        kstep(ks + 3, 1, 2, true, true, true, true);
+        kstep(ks + 4, 3, 4, true, true, true, true);
+      }
+      int sX = 0, sY = 1;
+      for (; ks + 3 < ksteps; ++ks) {
+        kstep(ks, sX, sY, true, true, true, true);
+        sX = next_slot(sX, 2);
+        sY = next_slot(sY, 2);
+      }
+      // the last three K-steps: Y(ksteps - 1) is the last unit to request
+      for (; ks < ksteps; ++ks) {
+        kstep(ks, sX, sY, ks + 1 < ksteps, ks + 2 < ksteps, false, ks + 2 < ksteps);
+        sX = next_slot(sX, 2);
+        sY = next_slot(sY, 2);
+      }
+      // the asm MFMAs' results are read by ordinary instructions next: let the last ones retire
+      asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
     } else {
-      // Two sub-steps per K-step (bf16 on 16x16x32 blocks: four lane groups with one chunk each; 8-bit
-      // operands: an MFMA consumes 64 values of K, two chunks per lane).  Same ring, shifted by a quarter step so that the
+      // Two sub-steps per K-step (32x32 blocks whose MFMA consumes half of the K-step).  Same ring, shifted by a quarter step so that the
       // work still falls into four equal regions of TM*TN/2 MFMAs, eight fragment reads and half a
       // tile of loads each: the hand-over barrier sits in the middle of the K-step; after it a wave
       // reads the first fragments of K-step ks+1 and issues Y(ks+2) into the slot of X(ks), which that

@@ -6,8 +6,8 @@
 // fwd_kernel and dz_kernel also exist for 8-bit (e4m3) copies of their operands.
 //
 // Orientation: the vocabulary (or d) runs along the MFMA M axis and tokens (or vocabulary
-// rows of dW) along N.  With the MFMA accumulator layouts (16x16 blocks for bf16, 32x32 for fp32
-// and e4m3) a lane then owns ONE token column per block and 4 (or 16) vocabulary entries of it, so
+// rows of dW) along N.  With the MFMA accumulator layouts (16x16 blocks for bf16 and e4m3, 32x32 for
+// fp32) a lane then owns ONE token column per block and 4 (or 16) vocabulary entries of it, so
 // the softmax statistics are reduced inside the lane and need two (or one) cross-lane steps per
 // tile; and a lane's four consecutive M entries are contiguous in the row-major outputs (dZ row,
 // dH row, dW row).
@@ -261,7 +261,8 @@ struct DzRows {
   __device__ static constexpr int offset(int i, int v) { return 32 * (i >> 1) + 4 * (i & 1) + v; }
 };
 
-// Epilogue of the bf16 dZ kernel (16x16 blocks, permuted W rows): dZ = g (onehot - p) in bf16;
+// Epilogue of the dZ kernel on 16x16 blocks with bf16 output (bf16 or e4m3 operands; permuted W rows):
+// dZ = g (onehot - p) in bf16;
 //  - dZ [token][vocabulary] leaves straight from registers, 16 bytes per lane and block pair (a token's
 //    64 contiguous bytes come from the four lane groups of one store);
 //  - dZT [vocabulary][token] needs consecutive tokens, which sit in different lanes: the whole tile is
@@ -396,10 +397,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   const int64_t pitchH = a.ldHc * Elem<E>::size;
   const int64_t pitchW = a.ldW * Elem<E>::size;
 
-  // With 16x16 blocks the rows of the W tile enter LDS in a permuted order (DzRows), chosen so that a
+  // With 16x16 blocks and bf16 output the rows of the W tile enter LDS in a permuted order (DzRows), chosen so that a
   // lane's accumulators of two neighbouring blocks are EIGHT consecutive vocabulary entries of its token:
   // 16 bytes of a dZ row, stored straight from registers.
-  constexpr bool kDirect = G::NB == 16;
+  constexpr bool kDirect = G::NB == 16 && std::is_same<EO, bf16_tag>::value;
   uint32_t offA[G::A_LD], offB[G::B_LD];
 #pragma unroll
   for (int q = 0; q < G::A_LD; ++q) {
@@ -418,7 +419,6 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
          static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
   if constexpr (kDirect) {
-    static_assert(!kDirect || std::is_same<EO, bf16_tag>::value, "the 16x16 form is the bf16 kernel");
     dz_epilogue_direct<G>(a, acc, m0, mrel0, n0, smem);
     return;
   }
@@ -655,21 +655,6 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
     }
     if (jg + 1 < G::TN / JG) lds_barrier();
   }
-}
-
-// Raises the kernel's dynamic LDS limit to `bytes`; asked of the runtime once per kernel and device
-// (the kernel is a template argument so that each one keeps its own record).
-template <auto kernel>
-hipError_t allow_lds(int bytes) {
-  constexpr int kMaxDev = 64;
-  static std::atomic<bool> done[kMaxDev];
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < kMaxDev && done[dev].load(std::memory_order_acquire)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess && dev >= 0 && dev < kMaxDev) done[dev].store(true, std::memory_order_release);
-  return e;
 }
 
 }  // namespace

@@ -298,6 +298,29 @@ def test_fp8_logits_variant(vocab_chunk):
     assert np.abs(np64(logps[1]) - o_ref).max() <= TOL_LOGP
 
 
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (256, "bf16"), (512, "f32"), (1152, "bf16"), (1664, "f32")])
+def test_fp8_logits_contraction_lengths(d, dtype):
+    """The e4m3 main loop over 1, 2, 4, 9 and 13 K-steps of 128 values (its prologue, the loop unrolled by the
+    ring's period, the variable-slot loop and the last three steps each taken or skipped), for both storage
+    types of H, W and dZ."""
+    cfg = wl.CONFIGS[1].scaled(P=2, G=3, T=112, d=d, V=1024 + 300, dtype=dtype)
+    inp = small_inputs(cfg)
+    eh, ew = _fp8_exponent(inp["H"]), _fp8_exponent(inp["W"])
+    H64, W64 = wl.as_f64(inp["H"]), wl.as_f64(inp["W"])
+    Hq, Wq = O.quantize_e4m3(H64, eh), O.quantize_e4m3(W64, ew)
+    gp = GpuProblem(cfg, inp["H"], inp["W"], inp["tok"], inp["lens"], flags=4, fp8_exp_h=eh, fp8_exp_w=ew)
+    logp, lse, ent, _, _ = gp.fwd()
+    assert gp.check() == 0
+    o_lp, o_lse, o_ent = O.lmhead_logprob_fwd(Hq, Wq, inp["tok"], inp["lens"], cfg.T)
+    for got, want in ((logp, o_lp), (lse, o_lse), (ent, o_ent)):
+        assert np.abs(np64(got) - want).max() <= TOL_LOGP
+    g = wl.synthetic_upstream_grad(cfg, inp["lens"])
+    dH, dW = gp.bwd(lse, to_device(g))
+    o_dH, o_dW = O.lmhead_logprob_bwd(H64, W64, inp["tok"], inp["lens"], cfg.T, g, H_logits=Hq, W_logits=Wq)
+    e_h, e_w = rel_fro(np64(dH), o_dH), rel_fro(np64(dW), o_dW)
+    assert e_h <= TOL_GRAD and e_w <= TOL_GRAD, (e_h, e_w)
+
+
 @pytest.mark.parametrize("vocab_chunk", [0, 2048])
 def test_bf16_dh_output_flag(vocab_chunk):
     """dH written as bf16: the fp32 sums over the vocabulary chunks rounded once at the end."""
