@@ -570,14 +570,18 @@ struct GemmTile {
     } else if constexpr (NB == 16 && FC == 2) {
       // e4m3 on 16x16x128 blocks: ONE MFMA per block pair consumes the whole K-step (32 cycles each, 64 per
       // K-step).  A second set of fragments does not fit the register file (2 x 128 registers), so there is
-      // one set, refilled behind the MFMAs that read it last: the A fragment of row block i right after the
-      // first MFMA of row block i + 1, the B fragment of column block j, during the last row block, right
-      // after MFMA (7, j + 1); the fragments of the last blocks (A[7], B[7]) arrive behind the first MFMA of
-      // the next K-step.  A refill is always placed behind the MFMA that FOLLOWS the register's last reader:
-      // when that one has been accepted by the matrix pipe the reader has long fetched its operands.
-      // Reads thus run one K-step ahead of the MFMAs: K-step c reads the tiles of K-step c + 1.  The barrier
-      // early in K-step c (behind its fourth MFMA) publishes the tiles of c + 1 and frees the two slots of c,
-      // which take Y(c + 2) and X(c + 3) at once: with X(c + 2) that is five units resident or in flight.
+      // one set, refilled behind the MFMAs that read it last.  The MFMAs of a K-step go over the column blocks
+      // in two halves (j < 4 for all rows i, then j >= 4 for all rows), which spreads the refills over the
+      // K-step (row-major order would pile all B refills up behind the last row: 2 KB of LDS reads per MFMA
+      // and wave; measured 1-2.5 % slower):
+      //   B[0..3] of K-step c + 1   during the second half of K-step c (their last readers end the first half)
+      //   A[i], i < 7, of c + 1     behind the first MFMA of row i + 1 of the second half
+      //   A[7], B[4..7] of c + 1    behind the first five MFMAs of K-step c + 1 itself
+      // A refill is always placed behind the MFMA that FOLLOWS the register's last reader: when that one has
+      // been accepted by the matrix pipe the reader has long fetched its operands.
+      // Reads thus run up to one K-step ahead of the MFMAs.  The barrier of K-step c (behind its ninth MFMA, when
+      // the last reads of the tiles of c have returned) publishes the tiles of c + 1 and frees the two slots of
+      // c, which take Y(c + 2) and X(c + 3) at once: with X(c + 2) that is five units resident or in flight.
       static_assert(NSUB == 1 && TM == TN && TM == 8 && A_LD == B_LD, "64 MFMAs per K-step");
       i32x8_t ga[TM], gb[TN];
       auto read_frag = [&](const char* slot, int r) {
@@ -615,28 +619,26 @@ struct GemmTile {
         const char* b0 = b_of(sx, sy);
         const char* a1 = a_of(sx1, sy1);
         const char* b1 = b_of(sx1, sy1);
+        constexpr int kBar = 8;   // MFMA behind which the hand-over barrier sits
 #pragma unroll
         for (int idx = 0; idx < TM * TN; ++idx) {
-          const int i = idx / TN, j = idx % TN;
+          const int h = idx / 32, r = idx % 32;
+          const int i = r / 4, j = 4 * h + r % 4;
           Elem<E>::mma(acc[i][j], ga[i], gb[j]);
           __builtin_amdgcn_sched_barrier(0);   // what follows stays behind this MFMA (see the refill rule above)
-          if (idx == 0) {
-            ga[TM - 1] = read_frag(a0, rA0 + (TM - 1) * NB);
-            gb[TN - 1] = read_frag(b0, rB0 + (TN - 1) * NB);
-          }
-          if (idx == 3 && next) {
-            __builtin_amdgcn_sched_barrier(0);
+          if (idx == 0) ga[TM - 1] = read_frag(a0, rA0 + (TM - 1) * NB);
+          if (idx >= 1 && idx <= 4) gb[3 + idx] = read_frag(b0, rB0 + (3 + idx) * NB);
+          if (idx == kBar && next) {
             if (x2) __builtin_amdgcn_s_waitcnt(wait_vm(A_LD)); else __builtin_amdgcn_s_waitcnt(kWaitVm0);
             __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
             __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
           }
           if (next) {
-            if (idx >= 8 && idx % 8 == 0) ga[idx / 8 - 1] = read_frag(a1, rA0 + (idx / 8 - 1) * NB);
-            if (idx > 8 * (TM - 1)) gb[idx - 8 * (TM - 1) - 1] = read_frag(b1, rB0 + (idx - 8 * (TM - 1) - 1) * NB);
-            // sixteen loads behind every third MFMA from the barrier on: Y(c + 2) into the slot of X(c),
-            // X(c + 3) into the slot of Y(c)
-            if (idx >= 4 && (idx - 4) % 3 == 0 && (idx - 4) / 3 < 2 * A_LD) {
-              const int q = (idx - 4) / 3;
+            if (idx == 33 || idx == 35 || idx == 37 || idx == 39) gb[(idx - 33) / 2] = read_frag(b1, rB0 + ((idx - 33) / 2) * NB);
+            if (idx >= 36 && idx % 4 == 0) ga[(idx - 36) / 4] = read_frag(a1, rA0 + ((idx - 36) / 4) * NB);
+            if (idx >= kBar && (idx - kBar) % 3 == 0 && (idx - kBar) / 3 < 2 * A_LD) {
+              const int q = (idx - kBar) / 3;
               if (q < A_LD) {
                 if (ldy) issue_y1(c + 2, sx, q);
               } else {
@@ -667,7 +669,7 @@ struct GemmTile {
 #pragma unroll
       for (int i = 0; i + 1 < TM; ++i) {
         ga[i] = read_frag(a_of(0, 1), rA0 + i * NB);
-        gb[i] = read_frag(b_of(0, 1), rB0 + i * NB);
+        if (i < TN / 2) gb[i] = read_frag(b_of(0, 1), rB0 + i * NB);
       }
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
