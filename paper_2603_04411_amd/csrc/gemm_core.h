@@ -57,6 +57,28 @@
 
 namespace lmhead {
 
+// Per-workgroup time stamps, compiled in only with -DLMHEAD_TRACE (a diagnostic build; nothing below costs an
+// instruction otherwise).  Lane 0 of wave 0 of workgroup b < 2^19 writes stamp k into word 16 b + k of a buffer the
+// host hands over with lmhead_debug_set_trace: trace_stamp the 100 MHz real-time counter, trace_cycles the shader
+// clock counter into the second half of the buffer (word 16 (2^19 + b) + k), so that the pair gives the clock
+// frequency over a section.  Each translation unit has its own pointer; only the one next to the forward kernel is
+// ever set, the others stay null and record nothing.
+#ifdef LMHEAD_TRACE
+constexpr unsigned kTraceWorkgroups = 1u << 19;
+static __device__ unsigned long long* g_trace;
+__device__ inline void trace_stamp(int k) {
+  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
+    g_trace[(size_t)blockIdx.x * 16 + k] = __builtin_amdgcn_s_memrealtime();
+}
+__device__ inline void trace_cycles(int k) {
+  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
+    g_trace[((size_t)kTraceWorkgroups + blockIdx.x) * 16 + k] = __builtin_readcyclecounter();
+}
+#else
+__device__ inline void trace_stamp(int) {}
+__device__ inline void trace_cycles(int) {}
+#endif
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -217,6 +239,21 @@ struct GemmTile {
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < VB; ++v) acc[i][j][v] = 0.f;
+  }
+
+  // The asm-statement MFMAs are invisible to the compiler's hazard recognizer: it inserts no wait states
+  // between an instruction that writes an accumulator register (the zero fill, which it is free to sink
+  // right in front of the first use) and an MFMA that reads it as its addend.  Called once before the first
+  // such MFMA: every accumulator is forced into its AGPR tuple here (asm statements keep their order), and
+  // the wait states follow.
+  __device__ static inline void settle(Acc& acc) {
+    if constexpr (NB == 16) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+      asm volatile("s_nop 7");
+    }
   }
 
   // acc += A_tile * B_tile^T over `ksteps` steps of 128 bytes.
@@ -506,8 +543,11 @@ struct GemmTile {
       } else {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
       }
+      trace_stamp(4);
       __builtin_amdgcn_s_barrier();
+      trace_stamp(5);
       frags_xy(lds + sX * SSTR, lds + sY * SSTR, 0, 0);
+      settle(acc);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
       // One steady-state K-step with X(ks), Y(ks) in slots sx, sy.  Entering it: X(ks), Y(ks) landed,
@@ -539,7 +579,11 @@ struct GemmTile {
         kstep(ks + 2, 4, 0);
         kstep(ks + 3, 1, 2);
         kstep(ks + 4, 3, 4);
+        if (ks == 0) trace_stamp(6);
+        if (ks == 5) trace_stamp(7);
+        if (ks == 10) { trace_stamp(8); trace_cycles(8); }
       }
+      trace_stamp(9); trace_cycles(9);
       for (; ks + 2 < ksteps; ++ks) {
         kstep(ks, sX, sY);
         sX = next_slot(sX, 2);
@@ -567,6 +611,7 @@ struct GemmTile {
       }
       // the asm MFMAs' results are read by ordinary instructions next: let the last ones retire
       asm volatile("s_nop 15\n\ts_nop 15");
+      trace_stamp(10);
     } else if constexpr (NB == 16 && FC == 2) {
       // e4m3 on 16x16x128 blocks: ONE MFMA per block pair consumes the whole K-step (32 cycles each, 64 per
       // K-step).  A second set of fragments does not fit the register file (2 x 128 registers), so there is
@@ -671,6 +716,7 @@ struct GemmTile {
         ga[i] = read_frag(a_of(0, 1), rA0 + i * NB);
         if (i < TN / 2) gb[i] = read_frag(b_of(0, 1), rB0 + i * NB);
       }
+      settle(acc);
       __builtin_amdgcn_sched_barrier(0);
       int ks = 0;
       // unrolled by the ring's period, so that every slot number is a constant (see the bf16 loop)

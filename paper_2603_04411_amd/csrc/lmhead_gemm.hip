@@ -64,6 +64,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   // runs over (policy, vocabulary tile), and neighbours in x still share the token block's rows of Hc
   int tx, nb;
   if (!xcd_tile_coords(blockIdx.x, a.ntiles * a.npol, nblk, kFwdMapBx, kFwdMapBy, tx, nb)) return;
+  trace_stamp(0);
   const int pol = tx / a.ntiles;
   const int tile = tx - pol * a.ntiles;
   const char* Wp = static_cast<const char*>(a.W[0]);
@@ -96,7 +97,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 
   typename G::Acc acc;
   G::zero(acc);
+  trace_stamp(1);
   G::run(acc, Wp + (int64_t)m0 * pitchW, offA, static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+  trace_stamp(2); trace_cycles(2);
 
   float mr[G::TN], sr[G::TN], tr[G::TN];
 #pragma unroll
@@ -226,6 +229,17 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     part[plane + base] = s;
     if (a.want_entropy && pol == 0) part[2 * plane + base] = t;
   }
+#ifdef LMHEAD_TRACE
+  trace_stamp(3);
+  trace_cycles(3);
+  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups) {
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    g_trace[(size_t)blockIdx.x * 16 + 11] = __builtin_amdgcn_s_getreg(4 | (15 << 11));   // HW_ID, bits 15:0
+    g_trace[(size_t)blockIdx.x * 16 + 12] = xcc;
+    g_trace[(size_t)blockIdx.x * 16 + 13] = ((unsigned long long)tx << 32) | (unsigned)nb;
+  }
+#endif
 }
 
 template <typename E>
@@ -710,3 +724,12 @@ hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s, int role)
 }
 
 }  // namespace lmhead
+
+#ifdef LMHEAD_TRACE
+// Diagnostic build only (not part of the boundary): hands the forward kernel a device buffer of
+// 2 x 2^19 x 16 64-bit words for its time stamps (see trace_stamp in gemm_core.h); NULL switches them off.
+extern "C" __attribute__((visibility("default"))) int lmhead_debug_set_trace(void* dev_buf) {
+  unsigned long long* p = static_cast<unsigned long long*>(dev_buf);
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(lmhead::g_trace), &p, sizeof(p));
+}
+#endif
