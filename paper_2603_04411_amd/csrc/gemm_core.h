@@ -61,7 +61,7 @@ namespace lmhead {
 // instruction otherwise).  Lane 0 of wave 0 of workgroup b < 2^19 writes stamp k into word 16 b + k of a buffer the
 // host hands over with lmhead_debug_set_trace: trace_stamp the 100 MHz real-time counter, trace_cycles the shader
 // clock counter into the second half of the buffer (word 16 (2^19 + b) + k), so that the pair gives the clock
-// frequency over a section.  Each translation unit has its own pointer; only the one next to the forward kernel is
+// frequency over a section (words 11-13 there hold the hardware ids and the tile coordinates).  Each translation unit has its own pointer; only the one next to the forward kernel is
 // ever set, the others stay null and record nothing.
 #ifdef LMHEAD_TRACE
 constexpr unsigned kTraceWorkgroups = 1u << 19;
@@ -545,7 +545,7 @@ struct GemmTile {
       }
       trace_stamp(4);
       __builtin_amdgcn_s_barrier();
-      trace_stamp(5);
+      trace_stamp(5); trace_cycles(5);
       frags_xy(lds + sX * SSTR, lds + sY * SSTR, 0, 0);
       settle(acc);
       __builtin_amdgcn_sched_barrier(0);
@@ -579,7 +579,7 @@ struct GemmTile {
         kstep(ks + 2, 4, 0);
         kstep(ks + 3, 1, 2);
         kstep(ks + 4, 3, 4);
-        if (ks == 0) trace_stamp(6);
+        if (ks == 0) { trace_stamp(6); trace_cycles(6); }
         if (ks == 5) trace_stamp(7);
         if (ks == 10) { trace_stamp(8); trace_cycles(8); }
       }

@@ -141,6 +141,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
   }
 
+  trace_stamp(11);
   // softmax statistics of this tile, inside the lane, 16 values of one token column at a time (one
   // 32x32 block or four 16x16 blocks); the scheduling barrier after each group keeps the
   // accumulator reads of later groups from being hoisted, so only 16 values are live in VGPRs at a time
@@ -197,6 +198,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
   }
 
+  trace_stamp(12);
   // combine the lane groups of a block (same token, other vocabulary rows), then the WGM waves via LDS
   float* red = reinterpret_cast<float*>(smem);  // [WGM][BN][3]
 #pragma unroll
@@ -215,6 +217,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       q[2] = tr[j];
     }
   }
+  trace_stamp(13);
   lds_barrier();
   for (int n = threadIdx.x; n < G::BN; n += G::NT) {
     float m = red[n * 3], s = red[n * 3 + 1], t = red[n * 3 + 2];
@@ -235,9 +238,10 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups) {
     unsigned xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    g_trace[(size_t)blockIdx.x * 16 + 11] = __builtin_amdgcn_s_getreg(4 | (15 << 11));   // HW_ID, bits 15:0
-    g_trace[(size_t)blockIdx.x * 16 + 12] = xcc;
-    g_trace[(size_t)blockIdx.x * 16 + 13] = ((unsigned long long)tx << 32) | (unsigned)nb;
+    unsigned long long* ids = g_trace + ((size_t)kTraceWorkgroups + blockIdx.x) * 16;   // next to the cycle counts
+    ids[11] = __builtin_amdgcn_s_getreg(4 | (15 << 11));   // HW_ID, bits 15:0
+    ids[12] = xcc;
+    ids[13] = ((unsigned long long)tx << 32) | (unsigned)nb;
   }
 #endif
 }

@@ -3,9 +3,9 @@
     python -m paper_2603_04411_amd.build --trace          # liblmhead_trace.so (same sources, -DLMHEAD_TRACE)
     python -m paper_2603_04411_amd.tile_trace c2 c1       # on the GPU
 
-The trace build writes, for each of the first 2^19 workgroups, the 100 MHz real-time counter at eleven points of
+The trace build writes, for each of the first 2^19 workgroups, the 100 MHz real-time counter at fourteen points of
 the tile (kernel entry, main-loop entry, first data landed, after 5 / 10 / 15 K-steps, end of the unrolled loop,
-end of the drain, epilogue start and end) and the shader clock counter at four of them, which gives the clock
+end of the drain, epilogue start, three points inside it, and its end) and the shader clock counter at six of them, which gives the clock
 frequency inside the loop and inside the epilogue separately.  Inputs are seeded and synthetic (N(0,1) hidden
 states, N(0, 0.02^2) weights, uniform lengths in [T/4, T]).  A diagnostic: it loads the trace library directly
 and is not used by the binding, the tests or the benchmark.
@@ -64,13 +64,15 @@ def main(names):
                 ("prologue barrier (all waves' loads landed)", 4, 5), ("K-steps 0-4", 5, 6), ("K-steps 5-9", 6, 7),
                 ("K-steps 10-14", 7, 8), (f"K-steps 15-{unrolled_end - 1} (steady state)", 8, 9),
                 (f"K-steps {unrolled_end}-{ksteps - 1} (variable-slot loop and drain)", 9, 10), ("final barrier", 10, 2),
-                ("epilogue", 2, 3), ("whole tile", 0, 3)]
+                ("epilogue: target-logit capture", 2, 11), ("epilogue: softmax statistics of 256 values per lane", 11, 12),
+                ("epilogue: lane-group merges, partials to LDS", 12, 13), ("epilogue: barrier, cross-wave merge, stores", 13, 3),
+                ("epilogue, all of it", 2, 3), ("whole tile", 0, 3)]
         print(f"{'section':74s} {'mean us':>8s} {'p10':>7s} {'p50':>7s} {'p90':>7s}")
         for label, a, b in segs:
             x = (t[:, b] - t[:, a]) * TICK_US
             x = x[(x > -1) & (x < 1000)]
             print(f"{label:74s} {x.mean():8.2f} {np.percentile(x, 10):7.2f} {np.percentile(x, 50):7.2f} {np.percentile(x, 90):7.2f}")
-        for label, a, b, steps in (("steady-state loop", 8, 9, unrolled_end - 15), ("epilogue", 2, 3, 0)):
+        for label, a, b, steps in (("K-steps 0-4", 5, 6, 5), ("steady-state loop", 8, 9, unrolled_end - 15), ("epilogue", 2, 3, 0)):
             us = (t[:, b] - t[:, a]) * TICK_US
             cc = (cy[:, b] - cy[:, a]).astype(np.float64)
             good = (us > 0.5) & (cc > 0)
@@ -79,7 +81,7 @@ def main(names):
                 line += f"; {cc[good].mean() / steps:.0f} clocks per K-step (2048 of them are MFMA issue cycles: {100 * 2048 * steps / cc[good].mean():.1f} % busy)"
             print(line)
         # do the workgroups of one XCD start together?  (sorted start times of the tiles of XCD 0)
-        xcc = t[:, 12] & 0xf
+        xcc = cy[:, 12] & 0xf
         st = np.sort(t[xcc == 0][:, 0])
         gaps = np.diff(st) * TICK_US
         print(f"XCD 0: {len(st)} tiles; gap between consecutive tile starts: p50 {np.percentile(gaps, 50):.2f} us, "
