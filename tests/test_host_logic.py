@@ -38,6 +38,14 @@ def test_every_declared_symbol_is_exported(lib):
     out = subprocess.run(["nm", "-D", "--defined-only", L.library_path()], capture_output=True, text=True).stdout
     exported = [ln.split()[-1] for ln in out.splitlines() if " T " in ln]
     assert sorted(exported) == sorted(declared)
+    # the diagnostic trace build (if it has been built) is the same ABI plus its one hook; the product library
+    # must not carry that hook
+    assert "lmhead_debug_set_trace" not in exported
+    trace = os.path.join(os.path.dirname(L.library_path()), "liblmhead_trace.so")
+    if os.path.exists(trace):
+        out = subprocess.run(["nm", "-D", "--defined-only", trace], capture_output=True, text=True).stdout
+        texp = [ln.split()[-1] for ln in out.splitlines() if " T " in ln]
+        assert sorted(texp) == sorted(declared + ["lmhead_debug_set_trace"])
 
 
 def test_descriptor_matches_c_layout():
