@@ -61,22 +61,25 @@ namespace lmhead {
 // instruction otherwise).  Lane 0 of wave 0 of workgroup b < 2^19 writes stamp k into word 16 b + k of a buffer the
 // host hands over with lmhead_debug_set_trace: trace_stamp the 100 MHz real-time counter, trace_cycles the shader
 // clock counter into the second half of the buffer (word 16 (2^19 + b) + k), so that the pair gives the clock
-// frequency over a section (words 11-13 there hold the hardware ids and the tile coordinates).  Each translation unit has its own pointer; only the one next to the forward kernel is
-// ever set, the others stay null and record nothing.
+// frequency over a section (words 11-13 there hold the hardware ids and the tile coordinates of a forward tile).
+// One kernel records at a time (g_trace_kind); GemmTile::run() is told its caller's kind.  Each translation unit
+// has its own copy of the two variables; only the one next to the LM-head kernels is ever set, the others stay
+// null and record nothing.
 #ifdef LMHEAD_TRACE
 constexpr unsigned kTraceWorkgroups = 1u << 19;
 static __device__ unsigned long long* g_trace;
-__device__ inline void trace_stamp(int k) {
-  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
+static __device__ int g_trace_kind;      // which kernel records: 1 forward, 2 dZ, 3 dH, 4 dW
+__device__ inline void trace_stamp(int k, int kind) {
+  if (g_trace && g_trace_kind == kind && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
     g_trace[(size_t)blockIdx.x * 16 + k] = __builtin_amdgcn_s_memrealtime();
 }
-__device__ inline void trace_cycles(int k) {
-  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
+__device__ inline void trace_cycles(int k, int kind) {
+  if (g_trace && g_trace_kind == kind && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups)
     g_trace[((size_t)kTraceWorkgroups + blockIdx.x) * 16 + k] = __builtin_readcyclecounter();
 }
 #else
-__device__ inline void trace_stamp(int) {}
-__device__ inline void trace_cycles(int) {}
+__device__ inline void trace_stamp(int, int) {}
+__device__ inline void trace_cycles(int, int) {}
 #endif
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -267,10 +270,10 @@ struct GemmTile {
   // lead to the operand that misses L2 more often (the one fewer concurrent workgroups share).
   __device__ static inline void run(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                     const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                    int ksteps, char* lds) {
+                                    int ksteps, char* lds, int trace_kind = 0) {
     static_assert(!kMaskB, "ragged rows need their limits");
     const int none[B_LD] = {};
-    run_rows(acc, A, offA, B, offB, none, 0x7fffffffu, ksteps, lds);
+    run_rows(acc, A, offA, B, offB, none, 0x7fffffffu, ksteps, lds, trace_kind);
   }
 
   // Same, with B given as one buffer of `bytesB` bytes (at most 2^31) that holds rows of differing
@@ -281,7 +284,8 @@ struct GemmTile {
   // LDS without touching memory.
   __device__ static inline void run_rows(Acc& acc, const char* __restrict__ A, const uint32_t (&offA)[A_LD],
                                          const char* __restrict__ B, const uint32_t (&offB)[B_LD],
-                                         const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds) {
+                                         const int (&limB)[B_LD], uint32_t bytesB, int ksteps, char* lds,
+                                         int trace_kind = 0) {
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int w = wave();
     const int l = lane();
@@ -543,9 +547,9 @@ struct GemmTile {
       } else {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
       }
-      trace_stamp(4);
+      trace_stamp(4, trace_kind);
       __builtin_amdgcn_s_barrier();
-      trace_stamp(5); trace_cycles(5);
+      trace_stamp(5, trace_kind); trace_cycles(5, trace_kind);
       frags_xy(lds + sX * SSTR, lds + sY * SSTR, 0, 0);
       settle(acc);
       __builtin_amdgcn_sched_barrier(0);
@@ -579,11 +583,11 @@ struct GemmTile {
         kstep(ks + 2, 4, 0);
         kstep(ks + 3, 1, 2);
         kstep(ks + 4, 3, 4);
-        if (ks == 0) { trace_stamp(6); trace_cycles(6); }
-        if (ks == 5) trace_stamp(7);
-        if (ks == 10) { trace_stamp(8); trace_cycles(8); }
+        if (ks == 0) { trace_stamp(6, trace_kind); trace_cycles(6, trace_kind); }
+        if (ks == 5) trace_stamp(7, trace_kind);
+        if (ks == 10) { trace_stamp(8, trace_kind); trace_cycles(8, trace_kind); }
       }
-      trace_stamp(9); trace_cycles(9);
+      trace_stamp(9, trace_kind); trace_cycles(9, trace_kind);
       for (; ks + 2 < ksteps; ++ks) {
         kstep(ks, sX, sY);
         sX = next_slot(sX, 2);
@@ -611,7 +615,7 @@ struct GemmTile {
       }
       // the asm MFMAs' results are read by ordinary instructions next: let the last ones retire
       asm volatile("s_nop 15\n\ts_nop 15");
-      trace_stamp(10);
+      trace_stamp(10, trace_kind);
     } else if constexpr (NB == 16 && FC == 2) {
       // e4m3 on 16x16x128 blocks: ONE MFMA per block pair consumes the whole K-step (32 cycles each, 64 per
       // K-step).  A second set of fragments does not fit the register file (2 x 128 registers), so there is

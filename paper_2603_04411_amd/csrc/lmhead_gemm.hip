@@ -64,7 +64,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
   // runs over (policy, vocabulary tile), and neighbours in x still share the token block's rows of Hc
   int tx, nb;
   if (!xcd_tile_coords(blockIdx.x, a.ntiles * a.npol, nblk, kFwdMapBx, kFwdMapBy, tx, nb)) return;
-  trace_stamp(0);
+  trace_stamp(0, 1);
   const int pol = tx / a.ntiles;
   const int tile = tx - pol * a.ntiles;
   const char* Wp = static_cast<const char*>(a.W[0]);
@@ -97,9 +97,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
 
   typename G::Acc acc;
   G::zero(acc);
-  trace_stamp(1);
-  G::run(acc, Wp + (int64_t)m0 * pitchW, offA, static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
-  trace_stamp(2); trace_cycles(2);
+  trace_stamp(1, 1);
+  G::run(acc, Wp + (int64_t)m0 * pitchW, offA, static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem, 1);
+  trace_stamp(2, 1); trace_cycles(2, 1);
 
   float mr[G::TN], sr[G::TN], tr[G::TN];
 #pragma unroll
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
   }
 
-  trace_stamp(11);
+  trace_stamp(11, 1);
   // softmax statistics of this tile, inside the lane, 16 values of one token column at a time (one
   // 32x32 block or four 16x16 blocks); the scheduling barrier after each group keeps the
   // accumulator reads of later groups from being hoisted, so only 16 values are live in VGPRs at a time
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     }
   }
 
-  trace_stamp(12);
+  trace_stamp(12, 1);
   // combine the lane groups of a block (same token, other vocabulary rows), then the WGM waves via LDS
   float* red = reinterpret_cast<float*>(smem);  // [WGM][BN][3]
 #pragma unroll
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
       q[2] = tr[j];
     }
   }
-  trace_stamp(13);
+  trace_stamp(13, 1);
   lds_barrier();
   for (int n = threadIdx.x; n < G::BN; n += G::NT) {
     float m = red[n * 3], s = red[n * 3 + 1], t = red[n * 3 + 2];
@@ -233,9 +233,9 @@ __global__ __launch_bounds__(Tile<E>::NT) void fwd_kernel(FwdArgs a) {
     if (a.want_entropy && pol == 0) part[2 * plane + base] = t;
   }
 #ifdef LMHEAD_TRACE
-  trace_stamp(3);
-  trace_cycles(3);
-  if (g_trace && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups) {
+  trace_stamp(3, 1);
+  trace_cycles(3, 1);
+  if (g_trace && g_trace_kind == 1 && threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups) {
     unsigned xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
     unsigned long long* ids = g_trace + ((size_t)kTraceWorkgroups + blockIdx.x) * 16;   // next to the cycle counts
@@ -320,6 +320,7 @@ __device__ inline void dz_epilogue_direct(const DzArgs& a, typename G::Acc& acc,
     hit |= (relj[j] >= m0) & (relj[j] < m0 + G::BM);
     relj[j] -= m0 + mb;                          // compared with compile-time constants
   }
+  trace_stamp(11, 2);
   // mode 0: no target of the wave's columns in this tile, no padding rows: dZ = -g p, with |g| folded into
   //         the exponent and the sign applied to the packed pair.
   // mode 1: a target somewhere in the tile: the one-hot term by a select (about a third of the tiles have
@@ -383,7 +384,9 @@ __device__ inline void dz_epilogue_direct(const DzArgs& a, typename G::Acc& acc,
     else
       emit(std::integral_constant<int, 2>{});
   }
+  trace_stamp(12, 2);
   lds_barrier();
+  trace_stamp(13, 2);
   // [vocabulary row][token] rows -> dZT
   constexpr int CPR = G::BN * 2 / 16;            // 16-byte chunks per staged row
   constexpr int RPP = G::NT / CPR;               // rows per pass
@@ -408,6 +411,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
   const int nblk = (nv + G::BN - 1) / G::BN;
   int mt, nb;
   if (!xcd_tile_coords(blockIdx.x, a.ntiles, nblk, kMapBx, kMapBy, mt, nb)) return;
+  trace_stamp(0, 2);
   const int64_t n0 = (int64_t)nb * G::BN;
   const int mrel0 = mt * G::BM;  // within the chunk
   const int m0 = a.c0 + mrel0;
@@ -434,10 +438,13 @@ __global__ __launch_bounds__(Tile<E>::NT) void dz_kernel(DzArgs a) {
 
   typename G::Acc acc;
   G::zero(acc);
+  trace_stamp(1, 2);
   G::run(acc, static_cast<const char*>(a.W) + (int64_t)m0 * pitchW, offA,
-         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem);
+         static_cast<const char*>(a.Hc) + n0 * pitchH, offB, ksteps, smem, 2);
+  trace_stamp(2, 2); trace_cycles(2, 2);
   if constexpr (kDirect) {
     dz_epilogue_direct<G>(a, acc, m0, mrel0, n0, smem);
+    trace_stamp(3, 2); trace_cycles(3, 2);
     return;
   }
 
@@ -623,7 +630,7 @@ __global__ __launch_bounds__(Tile<E>::NT) void gemm_t_kernel(GemmTArgs a) {
   typename G::Acc acc;
   G::zero(acc);
   G::run(acc, static_cast<const char*>(a.A) + (int64_t)m0 * pitchA + (int64_t)k_first * G::KB, offA,
-         static_cast<const char*>(a.B) + n0 * pitchB + (int64_t)k_first * G::KB, offB, ksteps, smem);
+         static_cast<const char*>(a.B) + n0 * pitchB + (int64_t)k_first * G::KB, offB, ksteps, smem, Role == 0 ? 3 : (Role == 1 ? 4 : 0));
 
   // The fp32 tile leaves through LDS as [n][m] rows, so that each output row segment (BM floats
   // = 1 KB) is read-modify-written by one wavefront instruction with 16 bytes per lane.  Rows go in
@@ -730,10 +737,13 @@ hipError_t launch_gemm_t(int dtype, const GemmTArgs& a, hipStream_t s, int role)
 }  // namespace lmhead
 
 #ifdef LMHEAD_TRACE
-// Diagnostic build only (not part of the boundary): hands the forward kernel a device buffer of
-// 2 x 2^19 x 16 64-bit words for its time stamps (see trace_stamp in gemm_core.h); NULL switches them off.
-extern "C" __attribute__((visibility("default"))) int lmhead_debug_set_trace(void* dev_buf) {
+// Diagnostic build only (not part of the boundary): hands the kernel of the given kind (1 forward, 2 dZ, 3 dH,
+// 4 dW) a device buffer of 2 x 2^19 x 16 64-bit words for its time stamps (see trace_stamp in gemm_core.h); NULL
+// switches them off.
+extern "C" __attribute__((visibility("default"))) int lmhead_debug_set_trace(void* dev_buf, int kind) {
   unsigned long long* p = static_cast<unsigned long long*>(dev_buf);
+  hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(lmhead::g_trace_kind), &kind, sizeof(kind));
+  if (e != hipSuccess) return (int)e;
   return (int)hipMemcpyToSymbol(HIP_SYMBOL(lmhead::g_trace), &p, sizeof(p));
 }
 #endif
